@@ -1,0 +1,23 @@
+"""Plain fp64 CPU oracle of the token-recall path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this package; it
+shares no code with the GPU path and never imports it.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .allocation import allocate, max_pool_same, split_budget, thresholds
+from .scoring import MODE_MAX, MODE_SUM, num_threads, row_stats, scores
+
+
+def recall(q, k, pool_kernels, budget, scale=None, mode=MODE_SUM):
+    """Whole path: Eq. 4, Eq. 5, then Algorithm 1 decided on the fp32-rounded scores (the
+    precision the GPU path decides in).  Returns (indices int64 ascending, score fp64[L])."""
+    score, _, _ = scores(q, k, scale=scale, mode=mode)
+    idx = allocate(score.astype(np.float32), pool_kernels, budget)
+    return idx, score
+
+
+__all__ = ["allocate", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
+           "num_threads", "recall", "MODE_SUM", "MODE_MAX"]

@@ -1,0 +1,55 @@
+"""Brute-force checker for tiny shapes: pure Python loops and math.exp, written straight from
+Eq. 4 / Eq. 5 / Algorithm 1 of the paper.  Independent of the oracle package (imports nothing
+from it) so that it can pin the oracle; far too slow for anything but tiny inputs."""
+from __future__ import annotations
+
+import math
+
+
+def brute_scores(q, k, Hq, Hkv, Lq, L, d, scale, mode="sum"):
+    """q[h][i][c], k[g][t][c] nested lists of Python floats -> score[t]."""
+    G = Hq // Hkv
+    score = [0.0] * L
+    for h in range(Hq):
+        g = h // G
+        for i in range(Lq):
+            logit = []
+            for t in range(L):
+                s = 0.0
+                for c in range(d):
+                    s += q[h][i][c] * k[g][t][c]
+                logit.append(s * scale)
+            m = max(logit)
+            e = [math.exp(x - m) for x in logit]
+            z = math.fsum(e)
+            for t in range(L):
+                p = e[t] / z
+                if mode == "sum":
+                    score[t] += p
+                else:
+                    score[t] = max(score[t], p)
+    return score
+
+
+def brute_pool(score, w):
+    L = len(score)
+    r = (w - 1) // 2
+    return [max(score[u] for u in range(max(0, t - r), min(L, t + r + 1))) for t in range(L)]
+
+
+def brute_allocate(score, kernels, budget):
+    L = len(score)
+    n = len(kernels)
+    shares = [budget // n + (1 if j < budget % n else 0) for j in range(n)]
+    chosen = set()
+    for w, share in zip(kernels, shares):
+        pooled = brute_pool(score, w)
+        ranked = sorted(range(L), key=lambda t: (-pooled[t], t))
+        got = 0
+        for t in ranked:
+            if got >= share:
+                break
+            if t not in chosen:
+                chosen.add(t)
+                got += 1
+    return sorted(chosen)
