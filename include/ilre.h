@@ -1,0 +1,116 @@
+/*
+ * libilre -- intermediate-layer token recall for context compression on MI355X (gfx950).
+ *
+ * Given the query states of a short question and the full-length key cache of one decoder
+ * layer (the retrieval layer l_R of the paper), score every context token, pool the scores
+ * with several kernel sizes, and return the indices of the tokens to keep.
+ *
+ *   Section 3.2, Eq. 4   A[h,i,t] = softmax_t( q[h,i,:] . K[g(h),t,:] * scale ), softmax over all L
+ *                        context positions, no mask; GQA: g(h) = h / (Hq/Hkv) (consecutive groups).
+ *   Section 3.2, Eq. 5   reduction over heads and queries to one score per context token:
+ *                        ILRE_SCORE_SUM  score[t] = sum_{h,i} A[h,i,t]   (default of this library)
+ *                        ILRE_SCORE_MAX  score[t] = max_{h,i} A[h,i,t]   (the equation as printed)
+ *   Section 3.2, Algorithm 1 (Context Allocation), stride-1 max-pool form: for each kernel size
+ *                        w_j in the order given, pooled_j[t] = max(score[u] : |u-t| <= (w_j-1)/2,
+ *                        0 <= u < L); among tokens not yet allocated take the B_j with the largest
+ *                        pooled_j (ties: lower index first); B_j = floor(B/n) (+1 for the first
+ *                        B mod n kernels); finally the allocated set sorted ascending.
+ *
+ * Conventions for every entry point
+ *   - returns an ilre_status; never throws, never aborts, never synchronises the device;
+ *   - "dev" pointers are device memory owned by the caller, "host" pointers host memory; the
+ *     library keeps no pointer after a call returns and frees nothing of the caller's;
+ *   - work is enqueued on opts->stream (NULL = the default stream) and the call returns at once;
+ *   - the library allocates no device memory: scratch comes from opts->workspace, sized by
+ *     ilre_workspace_bytes() for the same shape arguments; calls that share a workspace must be
+ *     ordered on one stream;
+ *   - inputs are read-only, outputs are fully overwritten, results are bitwise reproducible from
+ *     run to run on the same device;
+ *   - Q and K must hold finite values.
+ *   - on error nothing is enqueued (argument errors) or the stream state is unspecified
+ *     (ILRE_EHIP); ilre_last_error() describes the last error of the calling thread.
+ */
+#ifndef ILRE_H
+#define ILRE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ILRE_OK = 0,
+    ILRE_EINVAL = 1,        /* null pointer, non-positive size, Hq % Hkv != 0, even / non-positive kernel size */
+    ILRE_EUNSUPPORTED = 2,  /* head_dim != 128, unknown dtype / score mode, budget or kernel size over the limits below */
+    ILRE_ENOMEM = 3,        /* workspace missing or smaller than ilre_workspace_bytes() */
+    ILRE_EHIP = 4           /* a HIP call failed; see ilre_last_error() */
+} ilre_status;
+
+typedef enum { ILRE_F32 = 0, ILRE_BF16 = 1 } ilre_dtype;
+typedef enum { ILRE_SCORE_SUM = 0, ILRE_SCORE_MAX = 1 } ilre_score_mode;
+
+#define ILRE_HEAD_DIM 128        /* the only supported head dimension */
+#define ILRE_MAX_BUDGET 8192     /* largest budget when budget < L (budget >= L needs L <= 8192) */
+#define ILRE_MAX_POOL_KERNEL 2047 /* largest pooling kernel size */
+#define ILRE_MAX_POOL_KERNELS 64 /* most kernel sizes in one call */
+
+typedef struct {
+    int32_t struct_size;     /* sizeof(ilre_opts), for versioning */
+    int32_t dtype;           /* ilre_dtype of q and k_cache */
+    int32_t n_pool_kernels;  /* length of pool_kernels (selection entry points) */
+    int32_t score_mode;      /* ilre_score_mode */
+    float scale;             /* softmax scale; 0 means 1/sqrt(d) */
+    int32_t reserved;
+    int64_t k_stride_head;   /* elements between kv heads of k_cache;  0 = contiguous [Hkv, L, d] */
+    int64_t k_stride_token;  /* elements between tokens of k_cache;    0 = contiguous */
+    int64_t q_stride_head;   /* elements between heads of q;           0 = contiguous [Hq, Lq, d] */
+    int64_t q_stride_token;  /* elements between query tokens of q;    0 = contiguous */
+    void *workspace;         /* dev, 256-byte aligned */
+    size_t workspace_bytes;
+    void *stream;            /* hipStream_t */
+} ilre_opts;
+
+/* Bytes of device workspace any entry point needs for this shape (host computation only).
+   out_bytes: host. */
+int ilre_workspace_bytes(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                         int32_t n_pool_kernels, int32_t dtype, size_t *out_bytes);
+
+/* The whole path: Eq. 4, Eq. 5, Algorithm 1.
+   q          dev  [Hq, Lq, d] (strides in opts), element type opts->dtype, innermost d contiguous
+   k_cache    dev  [Hkv, L, d] (strides in opts; token-major [L, Hkv, d] is expressible)
+   pool_kernels host, opts->n_pool_kernels odd sizes >= 1, processed in this order
+   out_idx    dev  min(budget, L) int32, ascending, unique
+   out_scores dev  L float, the un-pooled per-token score of Eq. 5 */
+int ilre_recall(const void *q, const void *k_cache,
+                int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                int32_t budget, const int32_t *pool_kernels,
+                int32_t *out_idx, float *out_scores, const ilre_opts *opts);
+
+/* Stage 1 (Eq. 4 row statistics): for every row r = h*Lq + i
+   row_max[r] = max_t logit, row_sumexp[r] = sum_t exp(logit - row_max[r]); both dev, Hq*Lq float. */
+int ilre_row_stats(const void *q, const void *k_cache,
+                   int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                   float *row_max, float *row_sumexp, const ilre_opts *opts);
+
+/* Stage 2 (Eq. 4 normalised, Eq. 5): recompute the logits, normalise with the given row
+   statistics and reduce over heads and queries.  row_max,row_sumexp: dev, as written by
+   ilre_row_stats.  out_scores: dev, L float. */
+int ilre_col_scores(const void *q, const void *k_cache,
+                    int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                    const float *row_max, const float *row_sumexp,
+                    float *out_scores, const ilre_opts *opts);
+
+/* Stages 3-4 (Algorithm 1): pooling, budgeted top-k with skip-allocated, ascending output.
+   scores: dev, L finite floats.  pool_kernels: host.  out_idx: dev, min(budget, L) int32. */
+int ilre_select(const float *scores, int64_t L, int32_t budget, const int32_t *pool_kernels,
+                int32_t *out_idx, const ilre_opts *opts);
+
+/* Message for the last non-OK status returned to the calling thread (static storage, never NULL). */
+const char *ilre_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ILRE_H */

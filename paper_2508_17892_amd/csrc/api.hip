@@ -1,0 +1,260 @@
+// C ABI of libilre: argument validation, workspace carving and kernel launches on the caller's
+// stream.  Host code only; the kernels live in scoring.hip and select.hip.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ilre_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int status, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+    size_t part_m, part_z, row_max, row_sumexp, partial, select, total;
+    ilre::SelectLayout sel;
+};
+
+Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, int n_kernels)
+{
+    Layout l{};
+    size_t off = 0;
+    l.part_m = off;
+    off = up256(off + (size_t)p.nsplit * nrows * sizeof(float));
+    l.part_z = off;
+    off = up256(off + (size_t)p.nsplit * nrows * sizeof(float));
+    l.row_max = off;
+    off = up256(off + (size_t)nrows * sizeof(float));
+    l.row_sumexp = off;
+    off = up256(off + (size_t)nrows * sizeof(float));
+    l.partial = off;
+    off = up256(off + (size_t)p.nunits * (size_t)L * sizeof(float));
+    l.select = off;
+    l.sel = ilre::make_select_layout(L, n_kernels > 0 ? n_kernels : 1);
+    off += l.sel.total;
+    l.total = off;
+    return l;
+}
+
+int check_shape(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d, int32_t dtype)
+{
+    if (L < 1 || Lq < 1 || Hq < 1 || Hkv < 1) return fail(ILRE_EINVAL, "L, Lq, Hq, Hkv must be positive");
+    if (Hq % Hkv != 0) return fail(ILRE_EINVAL, "Hq (%d) must be a multiple of Hkv (%d)", Hq, Hkv);
+    if (L > 0x7FFFFFFFll) return fail(ILRE_EUNSUPPORTED, "L must fit an int32 index");
+    if (d != ILRE_HEAD_DIM) return fail(ILRE_EUNSUPPORTED, "head_dim %d unsupported (only %d)", d, ILRE_HEAD_DIM);
+    if (dtype != ILRE_F32 && dtype != ILRE_BF16) return fail(ILRE_EUNSUPPORTED, "unknown dtype %d", dtype);
+    if ((int64_t)Hq * Lq > 0x3FFFFFFF) return fail(ILRE_EUNSUPPORTED, "too many query rows");
+    return ILRE_OK;
+}
+
+int check_kernels(int64_t L, int32_t budget, const int32_t *pool_kernels, int32_t n)
+{
+    if (!pool_kernels) return fail(ILRE_EINVAL, "pool_kernels is null");
+    if (n < 1) return fail(ILRE_EINVAL, "n_pool_kernels must be positive");
+    if (n > ILRE_MAX_POOL_KERNELS) return fail(ILRE_EUNSUPPORTED, "more than %d pooling kernels", ILRE_MAX_POOL_KERNELS);
+    if (budget < 1) return fail(ILRE_EINVAL, "budget must be positive");
+    for (int j = 0; j < n; ++j) {
+        if (pool_kernels[j] < 1 || pool_kernels[j] % 2 == 0)
+            return fail(ILRE_EINVAL, "pooling kernel size %d must be odd and >= 1", pool_kernels[j]);
+        if (pool_kernels[j] > ILRE_MAX_POOL_KERNEL)
+            return fail(ILRE_EUNSUPPORTED, "pooling kernel size %d over the limit %d", pool_kernels[j], ILRE_MAX_POOL_KERNEL);
+    }
+    const int64_t n_out = budget < L ? budget : L;
+    if (n_out > ILRE_MAX_BUDGET)
+        return fail(ILRE_EUNSUPPORTED, "min(budget, L) = %lld over the limit %d", (long long)n_out, ILRE_MAX_BUDGET);
+    return ILRE_OK;
+}
+
+int check_opts(const ilre_opts *o)
+{
+    if (!o) return fail(ILRE_EINVAL, "opts is null");
+    if (o->struct_size != (int32_t)sizeof(ilre_opts))
+        return fail(ILRE_EINVAL, "opts->struct_size %d != %zu", o->struct_size, sizeof(ilre_opts));
+    if (o->score_mode != ILRE_SCORE_SUM && o->score_mode != ILRE_SCORE_MAX)
+        return fail(ILRE_EUNSUPPORTED, "unknown score_mode %d", o->score_mode);
+    if (!(o->scale >= 0.f) || isinf(o->scale)) return fail(ILRE_EINVAL, "scale must be finite and >= 0 (0 = 1/sqrt(d))");
+    return ILRE_OK;
+}
+
+int check_workspace(const ilre_opts *o, size_t need)
+{
+    if (!o->workspace) return fail(ILRE_ENOMEM, "workspace is null (%zu bytes needed)", need);
+    if (((uintptr_t)o->workspace & 255) != 0) return fail(ILRE_EINVAL, "workspace must be 256-byte aligned");
+    if (o->workspace_bytes < need)
+        return fail(ILRE_ENOMEM, "workspace has %zu bytes, %zu needed", o->workspace_bytes, need);
+    return ILRE_OK;
+}
+
+// Fills the part of ScoreArgs that describes Q and K; validates strides and alignment (the kernels
+// read 16-byte chunks).
+int fill_qk(ilre::ScoreArgs &a, const void *q, const void *k, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+            const ilre_opts *o)
+{
+    if (!q || !k) return fail(ILRE_EINVAL, "q or k_cache is null");
+    const int es = o->dtype == ILRE_BF16 ? 2 : 4;
+    a.q = q;
+    a.k = k;
+    a.L = L;
+    a.Lq = Lq;
+    a.Hq = Hq;
+    a.Hkv = Hkv;
+    a.G = Hq / Hkv;
+    a.q_stride_token = o->q_stride_token ? o->q_stride_token : d;
+    a.q_stride_head = o->q_stride_head ? o->q_stride_head : (int64_t)Lq * d;
+    a.k_stride_token = o->k_stride_token ? o->k_stride_token : d;
+    a.k_stride_head = o->k_stride_head ? o->k_stride_head : L * (int64_t)d;
+    const int64_t strides[4] = {a.q_stride_token, a.q_stride_head, a.k_stride_token, a.k_stride_head};
+    for (int64_t s : strides) {
+        if (s < d)
+            return fail(ILRE_EINVAL, "strides must be >= d (rows may not overlap)");
+        if ((s * es) % 16 != 0) return fail(ILRE_EINVAL, "strides must be multiples of 16 bytes");
+    }
+    if (((uintptr_t)q & 15) || ((uintptr_t)k & 15)) return fail(ILRE_EINVAL, "q and k_cache must be 16-byte aligned");
+    const float scale = o->scale > 0.f ? o->scale : 1.0f / sqrtf((float)d);
+    a.c = scale * 1.4426950408889634f;
+    return ILRE_OK;
+}
+
+void fill_plan(ilre::ScoreArgs &a, const ilre::ScorePlan &p)
+{
+    a.rows_per_group = p.rows_per_group;
+    a.nqb = p.nqb;
+    a.nsplit = p.nsplit;
+    a.ntiles = p.ntiles;
+    a.tiles_per_split = p.tiles_per_split;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(ILRE_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ilre_last_error(void) { return g_err; }
+
+int ilre_workspace_bytes(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d, int32_t n_pool_kernels,
+                         int32_t dtype, size_t *out_bytes)
+{
+    if (!out_bytes) return fail(ILRE_EINVAL, "out_bytes is null");
+    int rc = check_shape(L, Lq, Hq, Hkv, d, dtype);
+    if (rc) return rc;
+    if (n_pool_kernels < 0 || n_pool_kernels > ILRE_MAX_POOL_KERNELS)
+        return fail(ILRE_EINVAL, "n_pool_kernels out of range");
+    const ilre::ScorePlan p = ilre::make_score_plan(dtype, L, Lq, Hq, Hkv);
+    *out_bytes = make_layout(p, L, (int64_t)Hq * Lq, n_pool_kernels).total;
+    return ILRE_OK;
+}
+
+int ilre_row_stats(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                   float *row_max, float *row_sumexp, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
+    if (!row_max || !row_sumexp) return fail(ILRE_EINVAL, "row_max or row_sumexp is null");
+    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
+    const int64_t nrows = (int64_t)Hq * Lq;
+    const Layout lay = make_layout(p, L, nrows, opts->n_pool_kernels > 0 ? opts->n_pool_kernels : 0);
+    if ((rc = check_workspace(opts, lay.part_z + (size_t)p.nsplit * nrows * sizeof(float)))) return rc;
+    ilre::ScoreArgs a{};
+    if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    fill_plan(a, p);
+    unsigned char *ws = (unsigned char *)opts->workspace;
+    a.part_m = (float *)(ws + lay.part_m);
+    a.part_z = (float *)(ws + lay.part_z);
+    const hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
+    return ILRE_OK;
+}
+
+int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                    const float *row_max, const float *row_sumexp, float *out_scores, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
+    if (!row_max || !row_sumexp || !out_scores) return fail(ILRE_EINVAL, "row_max, row_sumexp or out_scores is null");
+    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
+    const int64_t nrows = (int64_t)Hq * Lq;
+    const Layout lay = make_layout(p, L, nrows, 0);
+    if ((rc = check_workspace(opts, lay.select))) return rc;
+    ilre::ScoreArgs a{};
+    if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    fill_plan(a, p);
+    unsigned char *ws = (unsigned char *)opts->workspace;
+    a.row_max = row_max;
+    a.row_sumexp = row_sumexp;
+    a.partial = (float *)(ws + lay.partial);
+    const hipError_t e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "column-score launch");
+    return ILRE_OK;
+}
+
+int ilre_select(const float *scores, int64_t L, int32_t budget, const int32_t *pool_kernels, int32_t *out_idx,
+                const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if (L < 1 || L > 0x7FFFFFFFll) return fail(ILRE_EINVAL, "L must be in [1, 2^31)");
+    if (!scores || !out_idx) return fail(ILRE_EINVAL, "scores or out_idx is null");
+    if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
+    // The selection region sits at the end of the workspace whatever the scoring shape was; used
+    // alone it starts at the workspace base.
+    const ilre::SelectLayout sel = ilre::make_select_layout(L, opts->n_pool_kernels);
+    if ((rc = check_workspace(opts, sel.total))) return rc;
+    const hipError_t e = ilre::launch_select(scores, L, budget, pool_kernels, opts->n_pool_kernels, out_idx,
+                                             opts->workspace, sel, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "selection launch");
+    return ILRE_OK;
+}
+
+int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                int32_t budget, const int32_t *pool_kernels, int32_t *out_idx, float *out_scores, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
+    if (!out_idx || !out_scores) return fail(ILRE_EINVAL, "out_idx or out_scores is null");
+    if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
+    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
+    const int64_t nrows = (int64_t)Hq * Lq;
+    const Layout lay = make_layout(p, L, nrows, opts->n_pool_kernels);
+    if ((rc = check_workspace(opts, lay.total))) return rc;
+    ilre::ScoreArgs a{};
+    if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    fill_plan(a, p);
+    unsigned char *ws = (unsigned char *)opts->workspace;
+    hipStream_t s = (hipStream_t)opts->stream;
+    a.part_m = (float *)(ws + lay.part_m);
+    a.part_z = (float *)(ws + lay.part_z);
+    float *row_max = (float *)(ws + lay.row_max);
+    float *row_sumexp = (float *)(ws + lay.row_sumexp);
+    hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, s);
+    if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
+    a.row_max = row_max;
+    a.row_sumexp = row_sumexp;
+    a.partial = (float *)(ws + lay.partial);
+    e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s);
+    if (e != hipSuccess) return hip_fail(e, "column-score launch");
+    e = ilre::launch_select(out_scores, L, budget, pool_kernels, opts->n_pool_kernels, out_idx, ws + lay.select, lay.sel, s);
+    if (e != hipSuccess) return hip_fail(e, "selection launch");
+    return ILRE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Internal declarations shared by the translation units of libilre (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ilre.h"
+
+namespace ilre {
+
+constexpr int kHeadDim = ILRE_HEAD_DIM;
+constexpr int kNumCU = 256;  // MI355X: 256 compute units in 8 XCDs
+constexpr int kNumXCD = 8;
+
+// ---------------------------------------------------------------- scoring (Eq. 4 / Eq. 5)
+
+// How one scoring pass is cut into workgroups.  A workgroup owns (kv head g, query block qb,
+// token split s): `waves` wavefronts of 32*nb query rows each, streaming its token tiles.
+struct ScorePlan {
+    int dtype;            // ilre_dtype
+    int waves;            // wavefronts per workgroup (4 or 8)
+    int nb;               // 32-row query blocks per wavefront
+    int rows_per_group;   // G * Lq query rows served by one kv head
+    int rows_per_wg;      // waves * nb * 32
+    int nqb;              // query blocks per kv group
+    int tile_tokens;      // tokens per LDS tile
+    int64_t ntiles;       // ceil(L / tile_tokens)
+    int nsplit;           // token splits per (g, qb)
+    int64_t tiles_per_split;
+    int nunits;           // Hkv * nqb  (partial score vectors of pass 2)
+    int grid;             // workgroups launched (a few may be idle padding for the XCD mapping)
+    size_t lds_bytes_stats, lds_bytes_cols;
+};
+
+struct ScoreArgs {
+    const void *q;
+    const void *k;
+    int64_t L;
+    int Lq, Hq, Hkv, G;
+    int64_t q_stride_head, q_stride_token, k_stride_head, k_stride_token;  // in elements
+    float c;  // scale * log2(e): logits leave the MFMA in raw units and are exponentiated base 2
+    int rows_per_group, nqb, nsplit;
+    int64_t ntiles, tiles_per_split;
+    // pass 1 (row statistics): per-split partial maxima (base-2 units) and sums
+    float *part_m, *part_z;  // [nsplit][Hq*Lq]
+    // pass 2 (column scores)
+    const float *row_max, *row_sumexp;  // [Hq*Lq]
+    float *partial;                     // [nunits][L]
+};
+
+ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv);
+
+hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp,
+                            hipStream_t s);
+hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores,
+                             hipStream_t s);
+
+// ---------------------------------------------------------------- selection (Algorithm 1)
+
+constexpr int kSelChunk = 4096;     // tokens per workgroup in the pooling passes
+constexpr int kSelBins = 4096;      // first-level histogram: top 12 bits of the ordered key
+constexpr int kSelSmall = 2048;     // refinement stops once this few boundary candidates remain
+constexpr int kSortCap = 16384;     // LDS sort capacity (>= ILRE_MAX_BUDGET + kSelSmall)
+
+struct SelectLayout {
+    size_t hist;      // uint32 [n][kSelBins]
+    size_t ctrl;      // SelCtrl [n]
+    size_t cand;      // uint64 [n][kSortCap]
+    size_t tie;       // uint64 [n][2][L]   (ping-pong lists of boundary-bin elements)
+    size_t total;
+};
+
+struct SelCtrl {
+    uint32_t want;        // K_j: candidates needed = min(B_j + sum_{i<j} B_i, L)
+    uint32_t share;       // B_j
+    uint32_t radius;      // (w_j - 1) / 2
+    uint32_t bin;         // first-level threshold bin
+    uint32_t above;       // elements in bins above the threshold bin
+    uint32_t need;        // still needed from the threshold bin
+    uint32_t cand_n;      // filled length of cand[j]
+    uint32_t tie_n;       // filled length of tie[j][0]
+    uint32_t sorted_n;    // candidates written back sorted
+    uint32_t pad[7];
+};
+
+SelectLayout make_select_layout(int64_t L, int n_kernels);
+
+hipError_t launch_select(const float *scores, int64_t L, int budget, const int32_t *pool_kernels, int n_kernels,
+                         int32_t *out_idx, void *workspace, const SelectLayout &lay, hipStream_t s);
+
+}  // namespace ilre

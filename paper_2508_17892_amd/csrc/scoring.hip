@@ -1,0 +1,442 @@
+// Scoring kernels of the token-recall path (paper Section 3.2, Eq. 4 and Eq. 5) for gfx950.
+//
+// Two passes over the key cache, both built on one MFMA skeleton:
+//   pass 1 (MODE 0, row statistics)  S^T = K_tile . Q^T : tokens are the MFMA rows, query rows the
+//           columns, so each lane owns one query row and sees 16 tokens of it per 32x32 block; the
+//           running maximum and sum of exponentials of Eq. 4's softmax stay in that lane's registers.
+//   pass 2 (MODE 1, column scores)   S = Q . K_tile^T : query rows are the MFMA rows, tokens the
+//           columns, so each lane owns one token and the Eq. 5 reduction over heads and queries is
+//           an in-lane sum (or max) over its 16 accumulator registers per block.
+// In both passes a wavefront keeps the fragments of its 32*NB query rows in registers for the whole
+// kernel; K tiles are staged once per workgroup in LDS (double buffered, rows padded by 16 bytes so
+// that the 16-byte fragment reads of 16 consecutive rows fall in distinct banks) and shared by all
+// query heads of the GQA group.  Logits leave the MFMA unscaled; scale*log2(e) is folded into the
+// single fma that feeds v_exp_f32.  No atomics anywhere: every reduction has a fixed order.
+#include "ilre_internal.h"
+
+#include <math.h>
+
+#include <type_traits>
+
+namespace ilre {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+constexpr float kNegBig = -1.0e30f;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int DT>
+struct Traits;
+
+// bf16: one 16-byte chunk holds 8 elements; v_mfma_f32_32x32x16_bf16 contracts 16 per issue
+// (lanes 0-31 supply k = 0..7, lanes 32-63 k = 8..15 of the same row).
+template <>
+struct Traits<ILRE_BF16> {
+    static constexpr int kElemBytes = 2;
+    static constexpr int kSteps = 8;
+    static constexpr int kChunksPerRow = 16;
+    // tokens per LDS tile: four 16-byte chunks staged per thread
+    static constexpr int tile_tokens(int waves) { return 16 * waves; }
+    static __device__ __forceinline__ void mma(f32x16 &acc, const uint4 &a, const uint4 &b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                      acc, 0, 0, 0);
+    }
+};
+
+// fp32: one chunk holds 4 elements; v_mfma_f32_32x32x2_f32 contracts 2 per issue (lanes 0-31 supply
+// k = 0, lanes 32-63 k = 1).  Element j of both operands' chunks is contracted by issue j, which pairs
+// identical k on the A and B side whatever order the k are visited in.
+template <>
+struct Traits<ILRE_F32> {
+    static constexpr int kElemBytes = 4;
+    static constexpr int kSteps = 16;
+    static constexpr int kChunksPerRow = 32;
+    static constexpr int tile_tokens(int waves) { return 16 * waves; }
+    static __device__ __forceinline__ void mma(f32x16 &acc, const uint4 &a, const uint4 &b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+    }
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Online update of one query row's running (max, sum of exponentials) with 16 new logits.
+// Logits are raw dot products; c = scale*log2(e) turns them into base-2 exponents.
+template <bool MASKED>
+__device__ __forceinline__ void row_update(const f32x16 &acc, float c, float &m, float &z, int64_t tok0, int64_t L)
+{
+    float s[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        s[v] = acc[v];
+        if (MASKED) {
+            const int64_t tok = tok0 + 8 * (v >> 2) + (v & 3);
+            if (tok >= L) s[v] = -INFINITY;
+        }
+    }
+    float smax = s[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) smax = fmaxf(smax, s[v]);
+    const float mnew = fmaxf(m, smax * c);
+    z *= fast_exp2(m - mnew);
+    m = mnew;
+    const float nm = -mnew;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; v += 4) {
+        p0 += fast_exp2(fmaf(s[v + 0], c, nm));
+        p1 += fast_exp2(fmaf(s[v + 1], c, nm));
+        p2 += fast_exp2(fmaf(s[v + 2], c, nm));
+        p3 += fast_exp2(fmaf(s[v + 3], c, nm));
+    }
+    z += (p0 + p1) + (p2 + p3);
+}
+
+// MODE 0: row statistics.  MODE 1: column scores (RMAX = 0 sum over rows, 1 max over rows).
+template <int DT, int NB, int WAVES, int MODE, int RMAX>
+__global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
+{
+    using T = Traits<DT>;
+    constexpr int NT = WAVES * 64;
+    constexpr int ES = T::kElemBytes;
+    constexpr int STEPS = T::kSteps;
+    constexpr int TN = T::tile_tokens(WAVES);
+    constexpr int CPR = T::kChunksPerRow;
+    constexpr int PITCH = CPR * 16 + 16;
+    constexpr int TILE_BYTES = TN * PITCH;
+    constexpr int NLOAD = TN * CPR / NT;
+    constexpr int TBLOCKS = TN / 32;
+    static_assert(TN * CPR % NT == 0, "tile must divide over the threads");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    // blockIdx -> (kv head, token split, query block).  Workgroups are dealt round-robin to the 8
+    // XCDs, so the query blocks that stream the same K range are given ids with equal id % 8 and
+    // consecutive id / 8: they run on one XCD at about the same time and share its L2.
+    const int xcd = blockIdx.x % kNumXCD;
+    const int slot = blockIdx.x / kNumXCD;
+    const int qb = slot % a.nqb;
+    const int64_t pair = (int64_t)(slot / a.nqb) * kNumXCD + xcd;
+    if (pair >= (int64_t)a.Hkv * a.nsplit) return;
+    const int g = (int)(pair / a.nsplit);
+    const int split = (int)(pair % a.nsplit);
+    const int64_t tile0 = (int64_t)split * a.tiles_per_split;
+    const int64_t tile1 = (tile0 + a.tiles_per_split < a.ntiles) ? tile0 + a.tiles_per_split : a.ntiles;
+    if (tile0 >= tile1) return;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int half = lane >> 5;
+    const int rl0 = qb * (WAVES * NB * 32) + wave * (NB * 32);
+    const int64_t nrows = (int64_t)a.Hq * a.Lq;
+
+    // Query fragments, resident for the whole kernel: lane holds, for each of its NB blocks, row
+    // l32 of the block, 16-byte chunk (2*step + half) of that row.
+    uint4 qf[NB][STEPS];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int rl = rl0 + b * 32 + l32;
+        if (rl < a.rows_per_group) {
+            const int h = g * a.G + rl / a.Lq;
+            const int i = rl % a.Lq;
+            const unsigned char *src =
+                (const unsigned char *)a.q + ((int64_t)h * a.q_stride_head + (int64_t)i * a.q_stride_token) * ES;
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) qf[b][st] = *(const uint4 *)(src + (st * 2 + half) * 16);
+        } else {
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) qf[b][st] = make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    const unsigned char *kbase = (const unsigned char *)a.k + (int64_t)g * a.k_stride_head * ES;
+    const int64_t krow_bytes = a.k_stride_token * ES;
+
+    uint4 stage[NLOAD];
+    auto fetch_tile = [&](int64_t tile) {
+#pragma unroll
+        for (int j = 0; j < NLOAD; ++j) {
+            const int cid = tid + j * NT;
+            const int64_t tok = tile * TN + cid / CPR;
+            stage[j] = (tok < a.L) ? *(const uint4 *)(kbase + tok * krow_bytes + (cid % CPR) * 16) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto stash_tile = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < NLOAD; ++j) {
+            const int cid = tid + j * NT;
+            *(uint4 *)(smem + buf * TILE_BYTES + (cid / CPR) * PITCH + (cid % CPR) * 16) = stage[j];
+        }
+    };
+
+    // pass-1 state: one (max, sum) per owned query row, in base-2 exponent units
+    float m[NB], z[NB];
+    // pass-2 state: per accumulator register the row's exponent offset -(max*log2e + log2 sum)
+    float noff[MODE == 1 ? NB : 1][16];
+    float *red = (float *)(smem + 2 * TILE_BYTES);  // [2][WAVES][TN], pass 2 only
+    const int unit = g * a.nqb + qb;
+
+    if (MODE == 0) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            m[b] = kNegBig;
+            z[b] = 0.f;
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rl = rl0 + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                float off = -INFINITY;  // padded rows have q = 0: exp2(0*c - inf) = 0
+                if (rl < a.rows_per_group) {
+                    const int64_t r = (int64_t)(g * a.G + rl / a.Lq) * a.Lq + rl % a.Lq;
+                    off = -(a.row_max[r] * kLog2e + __log2f(a.row_sumexp[r]));
+                }
+                noff[b][v] = off;
+            }
+        }
+    }
+
+    // Sum (or max) over the wavefronts of the column results of a finished tile, in wave order.
+    auto flush_columns = [&](int64_t tile, int rbuf) {
+        if (tid < TN) {
+            const int64_t tok = tile * TN + tid;
+            if (tok < a.L) {
+                float acc = red[(rbuf * WAVES + 0) * TN + tid];
+#pragma unroll
+                for (int w = 1; w < WAVES; ++w) {
+                    const float x = red[(rbuf * WAVES + w) * TN + tid];
+                    acc = RMAX ? fmaxf(acc, x) : acc + x;
+                }
+                a.partial[(int64_t)unit * a.L + tok] = acc;
+            }
+        }
+    };
+
+    fetch_tile(tile0);
+    stash_tile(0);
+    __syncthreads();
+
+    // One tile: prefetch the next one into registers, consume the current one from LDS, park the
+    // prefetched one in the other buffer.  RAGGED is only ever true for the last tile of the context.
+    auto do_tile = [&](int64_t tile, auto ragged_tag) {
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        const int it = (int)(tile - tile0);
+        const int cur = it & 1;
+        const bool more = tile + 1 < tile1;
+        if (more) fetch_tile(tile + 1);
+        if (MODE == 1 && it > 0) flush_columns(tile - 1, cur ^ 1);
+
+        const unsigned char *tbuf = smem + cur * TILE_BYTES;
+#pragma unroll
+        for (int tb = 0; tb < TBLOCKS; ++tb) {
+            uint4 kf[STEPS];
+            const unsigned char *rowp = tbuf + (tb * 32 + l32) * PITCH + half * 16;
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) kf[st] = *(const uint4 *)(rowp + st * 32);
+
+            if (MODE == 0) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int st = 0; st < STEPS; ++st) T::mma(acc, kf[st], qf[b][st]);
+                    row_update<RAGGED>(acc, a.c, m[b], z[b], tile * TN + tb * 32 + 4 * half, a.L);
+                }
+            } else {
+                float col = 0.f;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int st = 0; st < STEPS; ++st) T::mma(acc, qf[b][st], kf[st]);
+                    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; v += 4) {
+                        const float e0 = fast_exp2(fmaf(acc[v + 0], a.c, noff[b][v + 0]));
+                        const float e1 = fast_exp2(fmaf(acc[v + 1], a.c, noff[b][v + 1]));
+                        const float e2 = fast_exp2(fmaf(acc[v + 2], a.c, noff[b][v + 2]));
+                        const float e3 = fast_exp2(fmaf(acc[v + 3], a.c, noff[b][v + 3]));
+                        if (RMAX) {
+                            p0 = fmaxf(p0, e0), p1 = fmaxf(p1, e1), p2 = fmaxf(p2, e2), p3 = fmaxf(p3, e3);
+                        } else {
+                            p0 += e0, p1 += e1, p2 += e2, p3 += e3;
+                        }
+                    }
+                    if (RMAX)
+                        col = fmaxf(col, fmaxf(fmaxf(p0, p1), fmaxf(p2, p3)));
+                    else
+                        col += (p0 + p1) + (p2 + p3);
+                }
+                const float other = __shfl_xor(col, 32);  // the other 16 rows of each block
+                col = RMAX ? fmaxf(col, other) : col + other;
+                if (half == 0) red[(cur * WAVES + wave) * TN + tb * 32 + l32] = col;
+            }
+        }
+
+        if (more) stash_tile(cur ^ 1);
+        __syncthreads();
+    };
+
+    // Only pass 1 has to mask the tokens past L (in pass 2 a lane is a token and is simply not
+    // stored); the ragged tile, if any, is the last tile of the last split.
+    const bool last_ragged = MODE == 0 && tile1 * TN > a.L;
+    const int64_t tile_full_end = last_ragged ? tile1 - 1 : tile1;
+    for (int64_t tile = tile0; tile < tile_full_end; ++tile) do_tile(tile, std::false_type{});
+    if (last_ragged) do_tile(tile1 - 1, std::true_type{});
+
+    if (MODE == 1) {
+        flush_columns(tile1 - 1, (int)((tile1 - 1 - tile0) & 1));
+    } else {
+        // The two half-waves saw disjoint tokens of the same query rows: merge, then one partial
+        // (max, sum) per row and split.
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const float mo = __shfl_xor(m[b], 32);
+            const float zo = __shfl_xor(z[b], 32);
+            const float mm = fmaxf(m[b], mo);
+            const float zz = z[b] * fast_exp2(m[b] - mm) + zo * fast_exp2(mo - mm);
+            const int rl = rl0 + b * 32 + l32;
+            if (half == 0 && rl < a.rows_per_group) {
+                const int64_t r = (int64_t)(g * a.G + rl / a.Lq) * a.Lq + rl % a.Lq;
+                a.part_m[(int64_t)split * nrows + r] = mm;
+                a.part_z[(int64_t)split * nrows + r] = zz;
+            }
+        }
+    }
+}
+
+// Merge the per-split partial statistics of each row (fixed split order) and convert to the
+// natural-log units of Eq. 4: row_max = max_t logit, row_sumexp = sum_t exp(logit - row_max).
+__global__ void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows, float *row_max,
+                                  float *row_sumexp)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= nrows) return;
+    float mm = kNegBig;
+    for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, part_m[(int64_t)s * nrows + r]);
+    float zz = 0.f;
+    for (int s = 0; s < nsplit; ++s) zz += part_z[(int64_t)s * nrows + r] * fast_exp2(part_m[(int64_t)s * nrows + r] - mm);
+    row_max[r] = mm * kLn2;
+    row_sumexp[r] = zz;
+}
+
+// score[t] = sum (or max) over the (kv head, query block) units of their partial column results.
+template <int RMAX>
+__global__ void reduce_units(const float *partial, int nunits, int64_t L, float *score)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= L) return;
+    float acc = partial[t];
+    for (int u = 1; u < nunits; ++u) {
+        const float x = partial[(int64_t)u * L + t];
+        acc = RMAX ? fmaxf(acc, x) : acc + x;
+    }
+    score[t] = acc;
+}
+
+template <int DT>
+constexpr size_t tile_lds_bytes(int waves)
+{
+    return 2 * (size_t)Traits<DT>::tile_tokens(waves) * (Traits<DT>::kChunksPerRow * 16 + 16);
+}
+
+template <typename K>
+hipError_t launch_score(K kernel, int grid, int threads, size_t lds, const ScoreArgs &a, hipStream_t s)
+{
+    hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
+{
+    ScorePlan p{};
+    p.dtype = dtype;
+    const int G = Hq / Hkv;
+    p.rows_per_group = G * Lq;
+    if (dtype == ILRE_F32) {
+        p.waves = 4;
+        p.nb = 1;
+    } else {
+        p.nb = 2;
+        // 8 waves (512 rows) unless 4 waves (256 rows) leave fewer padded rows
+        const int64_t pad8 = ((p.rows_per_group + 511) / 512) * 512;
+        const int64_t pad4 = ((p.rows_per_group + 255) / 256) * 256;
+        p.waves = pad4 < pad8 ? 4 : 8;
+    }
+    p.tile_tokens = dtype == ILRE_F32 ? Traits<ILRE_F32>::tile_tokens(p.waves) : Traits<ILRE_BF16>::tile_tokens(p.waves);
+    p.rows_per_wg = p.waves * p.nb * 32;
+    p.nqb = (p.rows_per_group + p.rows_per_wg - 1) / p.rows_per_wg;
+    p.ntiles = (L + p.tile_tokens - 1) / p.tile_tokens;
+    p.nunits = Hkv * p.nqb;
+    // enough splits for one workgroup of 8 waves (two of 4 waves) per compute unit
+    const int target = kNumCU * (p.waves == 8 ? 1 : 2);
+    int64_t nsplit = (target + p.nunits / 2) / p.nunits;
+    if (nsplit < 1) nsplit = 1;
+    if (nsplit > p.ntiles) nsplit = p.ntiles;
+    p.tiles_per_split = (p.ntiles + nsplit - 1) / nsplit;
+    p.nsplit = (int)((p.ntiles + p.tiles_per_split - 1) / p.tiles_per_split);
+    const int64_t pairs = (int64_t)Hkv * p.nsplit;
+    p.grid = (int)(((pairs + kNumXCD - 1) / kNumXCD) * kNumXCD * p.nqb);
+    const size_t tiles = dtype == ILRE_F32 ? tile_lds_bytes<ILRE_F32>(p.waves) : tile_lds_bytes<ILRE_BF16>(p.waves);
+    p.lds_bytes_stats = tiles;
+    p.lds_bytes_cols = tiles + 2 * (size_t)p.waves * p.tile_tokens * sizeof(float);
+    return p;
+}
+
+hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp, hipStream_t s)
+{
+    hipError_t e;
+    const size_t lds = p.lds_bytes_stats;
+    if (p.dtype == ILRE_F32)
+        e = launch_score(score_kernel<ILRE_F32, 1, 4, 0, 0>, p.grid, 256, lds, a, s);
+    else if (p.waves == 4)
+        e = launch_score(score_kernel<ILRE_BF16, 2, 4, 0, 0>, p.grid, 256, lds, a, s);
+    else
+        e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
+    if (e != hipSuccess) return e;
+    const int64_t nrows = (int64_t)a.Hq * a.Lq;
+    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
+                       a.nsplit, nrows, row_max, row_sumexp);
+    return hipGetLastError();
+}
+
+hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s)
+{
+    hipError_t e;
+    const size_t lds = p.lds_bytes_cols;
+    const bool mx = score_mode == ILRE_SCORE_MAX;
+    if (p.dtype == ILRE_F32)
+        e = mx ? launch_score(score_kernel<ILRE_F32, 1, 4, 1, 1>, p.grid, 256, lds, a, s)
+               : launch_score(score_kernel<ILRE_F32, 1, 4, 1, 0>, p.grid, 256, lds, a, s);
+    else if (p.waves == 4)
+        e = mx ? launch_score(score_kernel<ILRE_BF16, 2, 4, 1, 1>, p.grid, 256, lds, a, s)
+               : launch_score(score_kernel<ILRE_BF16, 2, 4, 1, 0>, p.grid, 256, lds, a, s);
+    else
+        e = mx ? launch_score(score_kernel<ILRE_BF16, 2, 8, 1, 1>, p.grid, 512, lds, a, s)
+               : launch_score(score_kernel<ILRE_BF16, 2, 8, 1, 0>, p.grid, 512, lds, a, s);
+    if (e != hipSuccess) return e;
+    const unsigned blocks = (unsigned)((a.L + 255) / 256);
+    if (mx)
+        hipLaunchKernelGGL(reduce_units<1>, dim3(blocks), dim3(256), 0, s, a.partial, p.nunits, a.L, out_scores);
+    else
+        hipLaunchKernelGGL(reduce_units<0>, dim3(blocks), dim3(256), 0, s, a.partial, p.nunits, a.L, out_scores);
+    return hipGetLastError();
+}
+
+}  // namespace ilre

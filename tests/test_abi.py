@@ -1,0 +1,101 @@
+"""The C-ABI library loads, exports every symbol include/ilre.h declares, and its host-side argument
+checks answer without a GPU.  No compute calls here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2508_17892_amd as il
+from paper_2508_17892_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    with open(os.path.join(ROOT, "include", "ilre.h")) as f:
+        text = f.read()
+    return sorted(set(re.findall(r"\b(ilre_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = il.load()
+    declared = _declared_functions()
+    assert set(declared) == set(il.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_opts_struct_matches_header_layout():
+    # int32 x4, float, int32, int64 x4, pointer, size_t, pointer on LP64
+    assert ctypes.sizeof(binding.IlreOpts) == 4 * 4 + 4 + 4 + 8 * 4 + 8 + 8 + 8
+    assert binding.IlreOpts.k_stride_head.offset == 24
+    assert binding.IlreOpts.workspace.offset == 56
+
+
+def test_workspace_bytes_grows_with_shape():
+    a = il.ilre_workspace_bytes(4096, 32, 32, 8, 128, 3, il.ILRE_F32)
+    b = il.ilre_workspace_bytes(1 << 20, 256, 32, 8, 128, 5, il.ILRE_BF16)
+    assert 0 < a < b < (1 << 30)
+
+
+@pytest.mark.parametrize("args,status", [
+    ((0, 32, 32, 8, 128, 3, 0), il.ILRE_EINVAL),
+    ((4096, 0, 32, 8, 128, 3, 0), il.ILRE_EINVAL),
+    ((4096, 32, 30, 8, 128, 3, 0), il.ILRE_EINVAL),
+    ((4096, 32, 32, 8, 64, 3, 0), il.ILRE_EUNSUPPORTED),
+    ((4096, 32, 32, 8, 128, 3, 7), il.ILRE_EUNSUPPORTED),
+    ((4096, 32, 32, 8, 128, 65, 0), il.ILRE_EINVAL),
+])
+def test_workspace_bytes_rejects_bad_shapes(args, status):
+    with pytest.raises(il.IlreError) as e:
+        il.ilre_workspace_bytes(*args)
+    assert e.value.status == status
+    assert il.ilre_last_error()
+
+
+def _opts(**kw):
+    o = binding.IlreOpts()
+    o.struct_size = ctypes.sizeof(binding.IlreOpts)
+    o.dtype = il.ILRE_BF16
+    o.n_pool_kernels = 2
+    for k, v in kw.items():
+        setattr(o, k, v)
+    return o
+
+
+def test_argument_errors_need_no_device():
+    lib = il.load()
+    kern = (ctypes.c_int32 * 2)(3, 7)
+    fake = ctypes.c_void_p(4096)          # never dereferenced: every call below fails validation first
+    o = _opts()
+    # null pointers
+    assert lib.ilre_recall(None, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(o)) in (il.ILRE_EINVAL, il.ILRE_ENOMEM)
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, None, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, None) == il.ILRE_EINVAL
+    # missing workspace
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(o)) == il.ILRE_ENOMEM
+    assert "workspace" in il.ilre_last_error()
+    # even kernel size, zero budget, budget over the limit, wrong struct size, bad score mode
+    even = (ctypes.c_int32 * 2)(3, 4)
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, even, fake, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 0, kern, fake, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_recall(fake, fake, 100000, 8, 8, 2, 128, 9000, kern, fake, fake, ctypes.byref(o)) == il.ILRE_EUNSUPPORTED
+    big = (ctypes.c_int32 * 2)(3, 4095)
+    assert lib.ilre_recall(fake, fake, 100000, 8, 8, 2, 128, 64, big, fake, fake, ctypes.byref(o)) == il.ILRE_EUNSUPPORTED
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(struct_size=8))) == il.ILRE_EINVAL
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(score_mode=5))) == il.ILRE_EUNSUPPORTED
+    # undersized and misaligned workspace
+    small = _opts(workspace=1 << 20, workspace_bytes=1024)
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(small)) == il.ILRE_ENOMEM
+    odd = _opts(workspace=(1 << 20) + 8, workspace_bytes=1 << 30)
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(odd)) == il.ILRE_EINVAL
+    # bad strides
+    ok_ws = dict(workspace=1 << 20, workspace_bytes=1 << 30)
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(k_stride_token=100, **ok_ws))) == il.ILRE_EINVAL
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(q_stride_token=132, **ok_ws))) == il.ILRE_EINVAL
+    # staged entry points validate too
+    assert lib.ilre_row_stats(fake, fake, 1000, 8, 8, 2, 128, None, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_col_scores(fake, fake, 1000, 8, 8, 2, 128, fake, fake, None, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_select(None, 1000, 64, kern, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_select(fake, 1000, 64, kern, fake, ctypes.byref(o)) == il.ILRE_ENOMEM

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Staged (row statistics, column scores, selection) and end to end."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import inputs
+import oracle
+import paper_2508_17892_amd as il
+from parity import ABS_TOL, REL_TOL, check_index_structure, index_set_report, score_errors, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+SHAPES = [
+    # name, L, Lq, Hq, Hkv, dtype, channel_scale
+    ("bf16_ragged_small", 1000, 8, 8, 2, "bf16", False),       # 32 rows/group: mostly padded rows, ragged tail
+    ("bf16_multi_tile", 5000, 64, 8, 2, "bf16", True),         # 256 rows/group: 4-wave workgroups
+    ("bf16_two_query_blocks", 3333, 160, 8, 1, "bf16", True),  # 1280 rows/group: 8-wave workgroups, 3 query blocks
+    ("f32_small", 777, 32, 8, 2, "f32", False),
+    ("f32_two_query_blocks", 2100, 48, 8, 2, "f32", True),     # 192 rows/group: 2 query blocks of 128
+    ("bf16_single_token", 1, 4, 4, 2, "bf16", False),
+    ("bf16_exact_tiles", 4096, 32, 32, 8, "bf16", False),
+]
+
+
+@pytest.mark.parametrize("name,L,Lq,Hq,Hkv,dtype,cs", SHAPES, ids=[s[0] for s in SHAPES])
+def test_staged_scoring(name, L, Lq, Hq, Hkv, dtype, cs):
+    _announce(f"staged_scoring {name} L={L} Lq={Lq} Hq={Hq} Hkv={Hkv} {dtype}")
+    inp = inputs.custom(L=L, Lq=Lq, Hq=Hq, Hkv=Hkv, d=128, dtype=dtype, n_spans=2 if L > 200 else 0,
+                        span_len=(8, 24), channel_scale=cs, seed=zlib.crc32(name.encode()) % 1000)
+    q, k = to_device(inp.q), to_device(inp.k)
+    want_score, want_max, want_sum = oracle.scores(inp.q, inp.k)
+
+    row_max, row_sumexp = il.ilre_row_stats(q, k)
+    torch.cuda.synchronize()
+    gm, gz = row_max.cpu().numpy().astype(np.float64), row_sumexp.cpu().numpy().astype(np.float64)
+    # the pair (max, sum) is compared through the log-sum-exp it encodes and directly
+    np.testing.assert_allclose(gm, want_max, rtol=0, atol=1e-4)
+    np.testing.assert_allclose(gz, want_sum, rtol=2e-4)
+
+    got = il.ilre_col_scores(q, k, row_max, row_sumexp)
+    torch.cuda.synchronize()
+    bad, worst = score_errors(got.cpu().numpy(), want_score)
+    assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
+    assert abs(float(got.double().sum()) - Hq * Lq) < 1e-3 * Hq * Lq
+
+    # column scores from the oracle's own row statistics (stage isolation)
+    got2 = il.ilre_col_scores(q, k, torch.from_numpy(want_max.astype(np.float32)).cuda(),
+                              torch.from_numpy(want_sum.astype(np.float32)).cuda())
+    bad, worst = score_errors(got2.cpu().numpy(), want_score)
+    assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
+
+    # Eq. 5 as printed: max over heads and queries
+    want_mx, _, _ = oracle.scores(inp.q, inp.k, mode=oracle.MODE_MAX)
+    got_mx = il.ilre_col_scores(q, k, row_max, row_sumexp, score_mode=il.ILRE_SCORE_MAX)
+    bad, worst = score_errors(got_mx.cpu().numpy(), want_mx)
+    assert bad == 0, f"max mode: {bad} scores out of tolerance, worst {worst:.2f}x"
+
+
+SELECT_CASES = [
+    # name, L, kernels, budget, kind
+    ("random_small", 3000, (3, 7, 15), 256, "random"),
+    ("random_multi_chunk", 50000, (1, 3, 7, 15, 31), 4096, "random"),
+    ("plateaus", 20000, (3, 7, 15, 31), 1024, "few_values"),
+    ("all_equal", 10000, (3, 7, 15), 100, "equal"),
+    ("budget_exceeds_L", 300, (3, 7), 1000, "random"),
+    ("L_smaller_than_kernel", 9, (31, 15), 4, "random"),
+    ("budget_not_divisible", 7000, (3, 7, 15), 256, "random"),
+    ("budget_below_kernel_count", 500, (1, 3, 5, 7), 3, "random"),
+    ("single_token", 1, (3,), 1, "random"),
+    ("wide_kernel", 30000, (2047, 1, 255), 600, "random"),
+    ("needle_like", 100000, (1, 3, 7, 15, 31), 4096, "needles"),
+    ("dense_background_ties", 200000, (3, 7, 15, 31), 4096, "narrow"),
+    ("max_budget", 40000, (3, 31), 8192, "random"),
+]
+
+
+def _scores_for(kind, L, rng):
+    if kind == "random":
+        return rng.random(L).astype(np.float32)
+    if kind == "few_values":
+        return (rng.integers(1, 9, size=L) / 16.0).astype(np.float32)
+    if kind == "equal":
+        return np.full(L, 0.125, dtype=np.float32)
+    if kind == "narrow":   # a dense background inside one binade, as real scores are
+        return (0.0078125 * (1.0 + 0.5 * rng.random(L))).astype(np.float32)
+    s = (0.008 * (1.0 + 0.3 * rng.standard_normal(L))).clip(1e-4).astype(np.float32)
+    for start in rng.integers(0, L - 300, size=20):
+        n = int(rng.integers(64, 256))
+        s[start:start + n] = (rng.random(n) * 8).astype(np.float32)
+    return s
+
+
+@pytest.mark.parametrize("name,L,kernels,budget,kind", SELECT_CASES, ids=[c[0] for c in SELECT_CASES])
+def test_select_exact_on_given_scores(name, L, kernels, budget, kind):
+    _announce(f"select {name} L={L} kernels={kernels} budget={budget}")
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    s = _scores_for(kind, L, rng)
+    want = oracle.allocate(s, kernels, budget)
+    got = il.ilre_select(torch.from_numpy(s).cuda(), budget, kernels)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    check_index_structure(got, L, budget)
+    assert got.tolist() == want.tolist()
+
+
+def _end_to_end(inp, kernels, budget):
+    wl = inp.workload
+    q, k = to_device(inp.q), to_device(inp.k)
+    idx, scores = il.ilre_recall(q, k, budget, kernels)
+    torch.cuda.synchronize()
+    idx, scores = idx.cpu().numpy(), scores.cpu().numpy()
+    want_scores, _, _ = oracle.scores(inp.q, inp.k)
+    bad, worst = score_errors(scores, want_scores)
+    assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
+    check_index_structure(idx, wl.L, budget)
+    rep = index_set_report(idx, want_scores, kernels, budget)
+    assert not rep["unexcused"], rep
+    # selection must agree exactly with the oracle's allocation run on the GPU's own scores
+    assert idx.tolist() == oracle.allocate(scores, kernels, budget).tolist()
+    return idx, scores, rep
+
+
+def test_end_to_end_cfg1():
+    _announce("end_to_end cfg1")
+    inp = inputs.config(1)
+    idx, scores, rep = _end_to_end(inp, inp.workload.pool_kernels, inp.workload.budget)
+    mask = inp.needle_mask
+    assert mask[idx].sum() >= 0.95 * mask.sum()
+
+
+def test_end_to_end_cfg2():
+    _announce("end_to_end cfg2")
+    inp = inputs.config(2)
+    idx, scores, rep = _end_to_end(inp, inp.workload.pool_kernels, inp.workload.budget)
+    mask = inp.needle_mask
+    assert mask[idx].sum() >= 0.95 * mask.sum()
+
+
+def test_end_to_end_ragged_bf16():
+    _announce("end_to_end ragged bf16")
+    inp = inputs.custom(L=9001, Lq=40, Hq=16, Hkv=4, d=128, dtype="bf16", n_spans=3, span_len=(16, 40),
+                        channel_scale=True, seed=77)
+    _end_to_end(inp, (1, 3, 7, 15, 31), 512)
+
+
+def test_token_major_strides():
+    _announce("token-major strided K and strided Q")
+    inp = inputs.custom(L=2500, Lq=16, Hq=8, Hkv=2, d=128, dtype="bf16", n_spans=1, span_len=(16, 16), seed=5)
+    q, k = to_device(inp.q), to_device(inp.k)
+    k_tm = k.permute(1, 0, 2).contiguous().permute(1, 0, 2)          # storage [L, Hkv, d]
+    q_pad = torch.zeros(8, 16, 256, dtype=q.dtype, device="cuda")[:, :, :128]
+    q_pad.copy_(q)
+    a_idx, a_sc = il.ilre_recall(q, k, 128, (3, 7))
+    b_idx, b_sc = il.ilre_recall(q_pad, k_tm, 128, (3, 7))
+    torch.cuda.synchronize()
+    assert torch.equal(a_idx, b_idx) and torch.equal(a_sc, b_sc)
+
+
+def test_bitwise_reproducible():
+    _announce("run-to-run determinism")
+    inp = inputs.custom(L=20000, Lq=64, Hq=8, Hkv=2, d=128, dtype="bf16", n_spans=4, span_len=(16, 64), seed=6)
+    q, k = to_device(inp.q), to_device(inp.k)
+    first = il.ilre_recall(q, k, 1024, (1, 3, 7, 15, 31))
+    for _ in range(3):
+        again = il.ilre_recall(q, k, 1024, (1, 3, 7, 15, 31))
+        torch.cuda.synchronize()
+        assert torch.equal(first[0], again[0]) and torch.equal(first[1], again[1])
+
+
+def test_custom_scale():
+    _announce("custom softmax scale")
+    inp = inputs.custom(L=1500, Lq=8, Hq=4, Hkv=2, d=128, dtype="bf16", seed=8)
+    q, k = to_device(inp.q), to_device(inp.k)
+    want, _, _ = oracle.scores(inp.q, inp.k, scale=0.05)
+    _, got = il.ilre_recall(q, k, 64, (3,), scale=0.05)
+    torch.cuda.synchronize()
+    bad, worst = score_errors(got.cpu().numpy(), want)
+    assert bad == 0, worst
