@@ -1,0 +1,133 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-recall hot path on one MI355X.
+
+One step = one ilre_recall call (row statistics, column scores, pooling, budgeted top-k) over the
+1M-token Llama-3.1-8B-shaped synthetic key cache (workload cfg5_1m), inputs resident in HBM.
+Prints ONE JSON line: whole-job context tokens/s, the roofline of the dominant kernel (timed with
+HIP events on the launch stream) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_MFMA_TFLOPS = 157.3  # fp32 matrix path (cfg 1 only)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, help="workload number (1-5); the metric is quoted on 5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (see profiles/)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on exactly one GPU (got --gpus {args.gpus}); "
+              "the path has no multi-GPU code. Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import inputs
+    import paper_2508_17892_amd as il
+    from parity import to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    il.load()  # fails loudly if the HIP library is not built
+
+    wl = inputs.CONFIGS[args.config]
+    t0 = time.time()
+    inp = inputs.generate(wl)
+    gen_s = time.time() - t0
+    q, k = to_device(inp.q), to_device(inp.k)
+    kernels, budget = wl.pool_kernels, wl.budget
+    dt = il.ILRE_BF16 if wl.dtype == "bf16" else il.ILRE_F32
+    ws = il.alloc_workspace(wl.L, wl.Lq, wl.Hq, wl.Hkv, wl.d, len(kernels), dt)
+    out_idx = torch.empty(min(budget, wl.L), dtype=torch.int32, device="cuda")
+    out_scores = torch.empty(wl.L, dtype=torch.float32, device="cuda")
+
+    def step():
+        il.ilre_recall(q, k, budget, kernels, workspace=ws, out_idx=out_idx, out_scores=out_scores)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = wl.L * args.steps / wall
+
+    # Per-stage device time over the same number of steps: the three staged entry points launch
+    # exactly the kernels ilre_recall launches; HIP events on the launch stream bracket each stage.
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        ev[i][0].record()
+        rmax, rsum = il.ilre_row_stats(q, k, workspace=ws)
+        ev[i][1].record()
+        sc = il.ilre_col_scores(q, k, rmax, rsum, workspace=ws)
+        ev[i][2].record()
+        il.ilre_select(sc, budget, kernels, workspace=ws, out_idx=out_idx)
+        ev[i][3].record()
+    torch.cuda.synchronize()
+    stage_ms = [float(np.mean([ev[i][s].elapsed_time(ev[i][s + 1]) for i in range(args.steps)])) for s in range(3)]
+
+    flops_per_pass = 2.0 * wl.Hq * wl.Lq * wl.L * wl.d
+    dom = 0 if stage_ms[0] >= stage_ms[1] else 1
+    dom_name = ("row_stats (score_kernel MODE 0)", "col_scores (score_kernel MODE 1)")[dom]
+    achieved = flops_per_pass / (stage_ms[dom] * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
+    roofline = {"bound": "mfma", "kernel": dom_name, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes,
+                "flops_per_launch": flops_per_pass, "launch_ms": round(stage_ms[dom], 4)}
+
+    result = {
+        "metric": "context tokens/sec recalled at L=1M (single GPU)" if args.config == 5
+                  else f"context tokens/sec recalled at L={wl.L} (single GPU)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "L": wl.L, "Lq": wl.Lq, "Hq": wl.Hq, "Hkv": wl.Hkv, "d": wl.d,
+                   "pool_kernels": list(kernels), "budget": budget, "needle_spans": wl.n_spans,
+                   "input_gen_s": round(gen_s, 1)},
+        "stage_ms": {"row_stats": round(stage_ms[0], 4), "col_scores": round(stage_ms[1], 4),
+                     "select": round(stage_ms[2], 4)},
+        "stage_tflops": {"row_stats": round(flops_per_pass / stage_ms[0] / 1e9, 1),
+                         "col_scores": round(flops_per_pass / stage_ms[1] / 1e9, 1)},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        Ls = min(args.cpu_sample_tokens, wl.L)
+        k_s = np.ascontiguousarray(inp.k[:, :Ls, :])
+        t0 = time.perf_counter()
+        oracle.recall(inp.q, k_s, kernels, budget)
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(Ls / cpu_s, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "seconds": round(cpu_s, 2),
+                                  "sample": f"whole path on the first {Ls} context tokens of {wl.name} "
+                                            f"(all {wl.Hq * wl.Lq} query rows, same kernels and budget)"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
