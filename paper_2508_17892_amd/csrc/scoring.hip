@@ -8,10 +8,13 @@
 //           columns, so each lane owns one token and the Eq. 5 reduction over heads and queries is
 //           an in-lane sum (or max) over its 16 accumulator registers per block.
 // In both passes a wavefront keeps the fragments of its 32*NB query rows in registers for the whole
-// kernel; K tiles are staged once per workgroup in LDS (double buffered, rows padded by 16 bytes so
-// that the 16-byte fragment reads of 16 consecutive rows fall in distinct banks) and shared by all
-// query heads of the GQA group.  Logits leave the MFMA unscaled; scale*log2(e) is folded into the
-// single fma that feeds v_exp_f32.  No atomics anywhere: every reduction has a fixed order.
+// kernel.  K tiles are copied once per workgroup from HBM straight into LDS (buffer loads with the LDS
+// flag, three buffers in flight, chunks XOR-swizzled so that the 16-byte fragment reads of 16
+// consecutive rows fall in distinct banks) and shared by all query heads of the GQA group.  The loop is
+// software pipelined: the MFMA chains of one 32-token block are interleaved, instruction by
+// instruction, with the exponentials of the block before it and with the LDS reads of the block after
+// it.  Logits leave the MFMA unscaled; scale*log2(e) is folded into the single fma that feeds
+// v_exp_f32.  No atomics anywhere: every reduction has a fixed order.
 #include "ilre_internal.h"
 
 #include <math.h>
@@ -100,21 +103,44 @@ __device__ __forceinline__ void row_update(const f32x16 &acc, float c, float &m,
     z += (p0 + p1) + (p2 + p3);
 }
 
+// Asynchronous 16-byte-per-lane copy from a buffer resource straight into LDS: lane l of the
+// wavefront lands at lds_addr + 16*l; bytes past the resource's num_records read as zero.  Tracked
+// by vmcnt.  Issued as inline assembly so that the compiler's conservative alias handling does not
+// put a full vmcnt wait in front of every later LDS read.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+__device__ __forceinline__ void lds_dma16(i32x4 rsrc, unsigned lds_addr, int voffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voffset), "s"(rsrc)
+                 : "memory");
+}
+
+__device__ __forceinline__ float quad_swap1(float x)  // lanes 0<->1, 2<->3 of every quad
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_swap2(float x)  // lanes 0<->2, 1<->3 of every quad
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true));
+}
+
 // MODE 0: row statistics.  MODE 1: column scores (RMAX = 0 sum over rows, 1 max over rows).
 template <int DT, int NB, int WAVES, int MODE, int RMAX>
 __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 {
     using T = Traits<DT>;
-    constexpr int NT = WAVES * 64;
     constexpr int ES = T::kElemBytes;
     constexpr int STEPS = T::kSteps;
     constexpr int TN = T::tile_tokens(WAVES);
     constexpr int CPR = T::kChunksPerRow;
-    constexpr int PITCH = CPR * 16 + 16;
-    constexpr int TILE_BYTES = TN * PITCH;
-    constexpr int NLOAD = TN * CPR / NT;
+    constexpr int ROWB = CPR * 16;
+    constexpr int TILE_BYTES = TN * ROWB;
+    constexpr int NLW = TN * CPR / 64 / WAVES;  // 1 KiB DMA issues per wavefront and tile
     constexpr int TBLOCKS = TN / 32;
-    static_assert(TN * CPR % NT == 0, "tile must divide over the threads");
+    constexpr int UNITS = TBLOCKS;              // pipeline units per tile: one per 32-token block
+    constexpr int NPART = WAVES * 2;            // partial column results per token (pass 2)
+    static_assert(TN * CPR % (64 * WAVES) == 0, "tile must divide over the wavefronts");
+    static_assert(UNITS % 2 == 0, "units alternate between two accumulators");
+    static_assert(TN == 16 * WAVES && NPART % 4 == 0, "column flush: 16 tokens per wavefront, 4 lanes per token");
 
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -159,31 +185,45 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         }
     }
 
+    // K tiles: three LDS buffers of TN rows, row r's 16-byte chunk c stored at chunk position
+    // c ^ (r & 15), so that the fragment reads of 16 consecutive rows fall in distinct banks while a
+    // wavefront's DMA still fills 1 KiB of consecutive LDS.
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const unsigned char *kbase = (const unsigned char *)a.k + (int64_t)g * a.k_stride_head * ES;
     const int64_t krow_bytes = a.k_stride_token * ES;
+    int dma_voff[NLW];
+#pragma unroll
+    for (int j = 0; j < NLW; ++j) {
+        const int pchunk = (wave * NLW + j) * 64 + lane;
+        const int row = pchunk / CPR, cpos = pchunk % CPR;
+        dma_voff[j] = (int)(row * krow_bytes) + (cpos ^ (row & 15)) * 16;
+    }
+    auto issue_tile = [&](int64_t tile, int buf) {
+        const int64_t tok0 = tile * TN;
+        const unsigned long long base = (unsigned long long)(kbase + tok0 * krow_bytes);
+        long long avail = (a.L - tok0 - 1) * krow_bytes + ROWB;  // bytes up to the end of row L-1
+        if (avail > 0xFFFFFFFFll) avail = 0xFFFFFFFFll;
+        i32x4 rsrc;
+        rsrc[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)base);
+        rsrc[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(base >> 32) & 0xFFFFu));
+        rsrc[2] = __builtin_amdgcn_readfirstlane((int)(unsigned)avail);
+        rsrc[3] = 0x00020000;
+#pragma unroll
+        for (int j = 0; j < NLW; ++j)
+            lds_dma16(rsrc, __builtin_amdgcn_readfirstlane(lds0 + buf * TILE_BYTES + (wave * NLW + j) * 1024), dma_voff[j]);
+    };
 
-    uint4 stage[NLOAD];
-    auto fetch_tile = [&](int64_t tile) {
+    // per-lane LDS byte offset of fragment chunk (2*st + half) of row l32 within a 32-row block,
+    // relative to the tile buffer being read; advanced from buffer to buffer in place
+    unsigned frag_addr[STEPS];
 #pragma unroll
-        for (int j = 0; j < NLOAD; ++j) {
-            const int cid = tid + j * NT;
-            const int64_t tok = tile * TN + cid / CPR;
-            stage[j] = (tok < a.L) ? *(const uint4 *)(kbase + tok * krow_bytes + (cid % CPR) * 16) : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto stash_tile = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < NLOAD; ++j) {
-            const int cid = tid + j * NT;
-            *(uint4 *)(smem + buf * TILE_BYTES + (cid / CPR) * PITCH + (cid % CPR) * 16) = stage[j];
-        }
-    };
+    for (int st = 0; st < STEPS; ++st) frag_addr[st] = lds0 + l32 * ROWB + (((2 * st + half) ^ (l32 & 15)) * 16);
 
     // pass-1 state: one (max, sum) per owned query row, in base-2 exponent units
     float m[NB], z[NB];
     // pass-2 state: per accumulator register the row's exponent offset -(max*log2e + log2 sum)
     float noff[MODE == 1 ? NB : 1][16];
-    float *red = (float *)(smem + 2 * TILE_BYTES);  // [2][WAVES][TN], pass 2 only
+    float *red = (float *)(smem + 3 * TILE_BYTES);  // [3][NPART][TN], pass 2 only
     const int unit = g * a.nqb + qb;
 
     if (MODE == 0) {
@@ -208,84 +248,132 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         }
     }
 
-    // Sum (or max) over the wavefronts of the column results of a finished tile, in wave order.
-    auto flush_columns = [&](int64_t tile, int rbuf) {
-        if (tid < TN) {
-            const int64_t tok = tile * TN + tid;
-            if (tok < a.L) {
-                float acc = red[(rbuf * WAVES + 0) * TN + tid];
+    // Pass 2: combine the NPART partial column results of a finished tile in a fixed order.  Wave w
+    // takes tokens 16w..16w+15, four lanes per token, each lane NPART/4 partials, then the quad.
+    auto flush_columns = [&](int64_t tile) {
+        const float *rb = red + (int)((tile - tile0) % 3) * NPART * TN;
+        const int tl = wave * 16 + (lane >> 2), part0 = (lane & 3) * (NPART / 4);
+        float acc = rb[part0 * TN + tl];
 #pragma unroll
-                for (int w = 1; w < WAVES; ++w) {
-                    const float x = red[(rbuf * WAVES + w) * TN + tid];
-                    acc = RMAX ? fmaxf(acc, x) : acc + x;
+        for (int k = 1; k < NPART / 4; ++k) {
+            const float x = rb[(part0 + k) * TN + tl];
+            acc = RMAX ? fmaxf(acc, x) : acc + x;
+        }
+        const float x1 = quad_swap1(acc);
+        acc = RMAX ? fmaxf(acc, x1) : acc + x1;
+        const float x2 = quad_swap2(acc);
+        acc = RMAX ? fmaxf(acc, x2) : acc + x2;
+        const int64_t tok = tile * TN + tl;
+        if ((lane & 3) == 0 && tok < a.L) a.partial[(int64_t)unit * a.L + tok] = acc;
+    };
+
+    // The softmax arithmetic of one finished 32x32 block ("unit": token block tb, query block b).
+    // It runs one unit behind the MFMAs, so that the matrix pipe works on unit u while the vector
+    // pipe exponentiates unit u-1 from the other accumulator.
+    float col = 0.f;  // pass 2: running column result of the token block over its NB query blocks
+    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, auto masked_tag, bool store) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (MODE == 0) {
+            row_update<MASKED>(acc, a.c, m[b], z[b], tile * TN + tb * 32 + 4 * half, a.L);
+        } else {
+            float e[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) e[v] = fast_exp2(fmaf(acc[v], a.c, noff[b][v]));
+            float p0 = e[0], p1 = e[1], p2 = e[2], p3 = e[3];
+#pragma unroll
+            for (int v = 4; v < 16; v += 4) {
+                if (RMAX) {
+                    p0 = fmaxf(p0, e[v]), p1 = fmaxf(p1, e[v + 1]), p2 = fmaxf(p2, e[v + 2]), p3 = fmaxf(p3, e[v + 3]);
+                } else {
+                    p0 += e[v], p1 += e[v + 1], p2 += e[v + 2], p3 += e[v + 3];
                 }
-                a.partial[(int64_t)unit * a.L + tok] = acc;
             }
+            const float part = RMAX ? fmaxf(fmaxf(p0, p1), fmaxf(p2, p3)) : (p0 + p1) + (p2 + p3);
+            if (b == 0)
+                col = part;
+            else
+                col = RMAX ? fmaxf(col, part) : col + part;
+            if (b == NB - 1 && store)
+                red[((int)((tile - tile0) % 3) * NPART + wave * 2 + half) * TN + tb * 32 + l32] = col;
         }
     };
 
-    fetch_tile(tile0);
-    stash_tile(0);
+    // Prologue: the first two tiles go to buffers 0 and 1.
+    issue_tile(tile0, 0);
+    if (tile0 + 1 < tile1) issue_tile(tile0 + 1, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // One tile: prefetch the next one into registers, consume the current one from LDS, park the
-    // prefetched one in the other buffer.  RAGGED is only ever true for the last tile of the context.
+    // acc[u & 1] receives unit u (a 32-token block against the wave's NB query blocks); the unit
+    // before the very first one is all -inf, which the softmax arithmetic turns into zeros.
+    f32x16 acc[2][NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[1][b][v] = -INFINITY;
+    }
+    uint4 kf[STEPS];
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st)
+        kf[st] = *(const uint4 *)(__attribute__((address_space(3))) unsigned char *)(size_t)frag_addr[st];
+
+    // One tile.  Its buffer and the next tile's are already published; the tile after that is
+    // requested now and published by the barrier at the end.  Per 32-token block the NB independent
+    // MFMA chains are interleaved step by step; as soon as a step's fragment has fed all chains it is
+    // refilled from LDS for the next block (for the last block, from the next tile's buffer).
+    // CUR_RAGGED is only ever true for the last tile of the context, and only in pass 1.
     auto do_tile = [&](int64_t tile, auto ragged_tag) {
-        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        constexpr bool CUR_RAGGED = decltype(ragged_tag)::value;
         const int it = (int)(tile - tile0);
-        const int cur = it & 1;
-        const bool more = tile + 1 < tile1;
-        if (more) fetch_tile(tile + 1);
-        if (MODE == 1 && it > 0) flush_columns(tile - 1, cur ^ 1);
+        if (tile + 2 < tile1) issue_tile(tile + 2, (it + 2) % 3);
+        if (MODE == 1 && it >= 2) flush_columns(tile - 2);
+        // byte distance from this tile's buffer to the next tile's
+        const int to_next = (it % 3 == 2) ? -2 * TILE_BYTES : TILE_BYTES;
 
-        const unsigned char *tbuf = smem + cur * TILE_BYTES;
 #pragma unroll
-        for (int tb = 0; tb < TBLOCKS; ++tb) {
-            uint4 kf[STEPS];
-            const unsigned char *rowp = tbuf + (tb * 32 + l32) * PITCH + half * 16;
+        for (int u = 0; u < UNITS; ++u) {
+            if (u == UNITS - 1) {
 #pragma unroll
-            for (int st = 0; st < STEPS; ++st) kf[st] = *(const uint4 *)(rowp + st * 32);
-
-            if (MODE == 0) {
+                for (int st = 0; st < STEPS; ++st) frag_addr[st] += to_next;
+            }
+            const int next_block = (u == UNITS - 1) ? 0 : (u + 1) * 32 * ROWB;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[u & 1][b][v] = 0.f;
+            }
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) {
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int st = 0; st < STEPS; ++st) T::mma(acc, kf[st], qf[b][st]);
-                    row_update<RAGGED>(acc, a.c, m[b], z[b], tile * TN + tb * 32 + 4 * half, a.L);
-                }
-            } else {
-                float col = 0.f;
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int st = 0; st < STEPS; ++st) T::mma(acc, qf[b][st], kf[st]);
-                    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
-#pragma unroll
-                    for (int v = 0; v < 16; v += 4) {
-                        const float e0 = fast_exp2(fmaf(acc[v + 0], a.c, noff[b][v + 0]));
-                        const float e1 = fast_exp2(fmaf(acc[v + 1], a.c, noff[b][v + 1]));
-                        const float e2 = fast_exp2(fmaf(acc[v + 2], a.c, noff[b][v + 2]));
-                        const float e3 = fast_exp2(fmaf(acc[v + 3], a.c, noff[b][v + 3]));
-                        if (RMAX) {
-                            p0 = fmaxf(p0, e0), p1 = fmaxf(p1, e1), p2 = fmaxf(p2, e2), p3 = fmaxf(p3, e3);
-                        } else {
-                            p0 += e0, p1 += e1, p2 += e2, p3 += e3;
-                        }
-                    }
-                    if (RMAX)
-                        col = fmaxf(col, fmaxf(fmaxf(p0, p1), fmaxf(p2, p3)));
+                    if (MODE == 0)
+                        T::mma(acc[u & 1][b], kf[st], qf[b][st]);
                     else
-                        col += (p0 + p1) + (p2 + p3);
+                        T::mma(acc[u & 1][b], qf[b][st], kf[st]);
                 }
-                const float other = __shfl_xor(col, 32);  // the other 16 rows of each block
-                col = RMAX ? fmaxf(col, other) : col + other;
-                if (half == 0) red[(cur * WAVES + wave) * TN + tb * 32 + l32] = col;
+                kf[st] = *(const uint4 *)((__attribute__((address_space(3))) unsigned char *)(size_t)frag_addr[st] + next_block);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                if (u == 0)
+                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, std::false_type{}, it > 0);
+                else
+                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, std::bool_constant<CUR_RAGGED>{}, true);
+            }
+            // ask the scheduler for: one MFMA (group), a slice of the vector work, and a fragment
+            // read after every NB-th MFMA
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, DT == ILRE_BF16 ? 1 : STEPS / 2, 0);
+                    if (b == NB - 1) __builtin_amdgcn_sched_group_barrier(0x100, STEPS / 8, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, MODE == 0 ? 8 : 6, 0);
+                }
             }
         }
 
-        if (more) stash_tile(cur ^ 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     };
 
@@ -295,9 +383,19 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     const int64_t tile_full_end = last_ragged ? tile1 - 1 : tile1;
     for (int64_t tile = tile0; tile < tile_full_end; ++tile) do_tile(tile, std::false_type{});
     if (last_ragged) do_tile(tile1 - 1, std::true_type{});
+    // drain the pipeline: the last unit of the last tile
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (last_ragged)
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::true_type{}, true);
+        else
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::false_type{}, true);
+    }
 
     if (MODE == 1) {
-        flush_columns(tile1 - 1, (int)((tile1 - 1 - tile0) & 1));
+        __syncthreads();
+        if (tile1 - tile0 >= 2) flush_columns(tile1 - 2);
+        flush_columns(tile1 - 1);
     } else {
         // The two half-waves saw disjoint tokens of the same query rows: merge, then one partial
         // (max, sum) per row and split.
@@ -349,7 +447,7 @@ __global__ void reduce_units(const float *partial, int nunits, int64_t L, float 
 template <int DT>
 constexpr size_t tile_lds_bytes(int waves)
 {
-    return 2 * (size_t)Traits<DT>::tile_tokens(waves) * (Traits<DT>::kChunksPerRow * 16 + 16);
+    return 3 * (size_t)Traits<DT>::tile_tokens(waves) * (Traits<DT>::kChunksPerRow * 16);
 }
 
 template <typename K>
@@ -395,7 +493,7 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     p.grid = (int)(((pairs + kNumXCD - 1) / kNumXCD) * kNumXCD * p.nqb);
     const size_t tiles = dtype == ILRE_F32 ? tile_lds_bytes<ILRE_F32>(p.waves) : tile_lds_bytes<ILRE_BF16>(p.waves);
     p.lds_bytes_stats = tiles;
-    p.lds_bytes_cols = tiles + 2 * (size_t)p.waves * p.tile_tokens * sizeof(float);
+    p.lds_bytes_cols = tiles + 3 * 2 * (size_t)p.waves * p.tile_tokens * sizeof(float);
     return p;
 }
 
