@@ -59,15 +59,16 @@ hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_m
 // ---------------------------------------------------------------- selection (Algorithm 1)
 
 constexpr int kSelChunk = 4096;     // tokens per workgroup in the pooling passes
-constexpr int kSelBins = 4096;      // first-level histogram: top 12 bits of the ordered key
-constexpr int kSelSmall = 2048;     // refinement stops once this few boundary candidates remain
-constexpr int kSortCap = 16384;     // LDS sort capacity (>= ILRE_MAX_BUDGET + kSelSmall)
+constexpr int kSelBins = 2048;      // histogram bins per level: 11 key bits
+constexpr int kSelSmall = 2048;     // boundary lists up to this long join the candidates unrefined
+constexpr int kCandCap = 10240;     // candidate list capacity (>= ILRE_MAX_BUDGET + kSelSmall)
 
 struct SelectLayout {
-    size_t hist;      // uint32 [n][kSelBins]
+    size_t hist;      // uint32 [2][n][kSelBins]  (level 1, level 2)
     size_t ctrl;      // SelCtrl [n]
-    size_t cand;      // uint64 [n][kSortCap]
-    size_t tie;       // uint64 [n][2][L]   (ping-pong lists of boundary-bin elements)
+    size_t done;      // uint32 [2]: workgroups finished per histogram level
+    size_t cand;      // uint64 [n][kCandCap]
+    size_t tie;       // uint64 [n][2][L]   (ping-pong lists of boundary elements)
     size_t total;
 };
 
@@ -75,13 +76,16 @@ struct SelCtrl {
     uint32_t want;        // K_j: candidates needed = min(B_j + sum_{i<j} B_i, L)
     uint32_t share;       // B_j
     uint32_t radius;      // (w_j - 1) / 2
-    uint32_t bin;         // first-level threshold bin
-    uint32_t above;       // elements in bins above the threshold bin
-    uint32_t need;        // still needed from the threshold bin
-    uint32_t cand_n;      // filled length of cand[j]
+    uint32_t bin1;        // level-1 bin (key bits 31..21) holding the K_j-th largest key
+    uint32_t above1;      // keys in bins above it
+    uint32_t need1;       // still needed from inside it
+    uint32_t bin2;        // level-2 bin (key bits 20..10) inside bin1
+    uint32_t above2;      // keys of bin1 in level-2 bins above bin2
+    uint32_t need2;       // still needed from inside (bin1, bin2)
+    uint32_t cand_n;      // filled length of cand[j] after collect
     uint32_t tie_n;       // filled length of tie[j][0]
-    uint32_t sorted_n;    // candidates written back sorted
-    uint32_t pad[7];
+    uint32_t total_n;     // candidates after refine
+    uint32_t pad[4];
 };
 
 SelectLayout make_select_layout(int64_t L, int n_kernels);

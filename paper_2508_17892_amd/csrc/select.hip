@@ -3,17 +3,23 @@
 // Algorithm 1 pools the scores per kernel size, takes a ranked candidate list per kernel and walks
 // it, skipping tokens an earlier kernel already allocated, until the kernel's share is filled.  The
 // share of kernel j can be met from its top K_j = B_j + (shares of the kernels before it) ranked
-// candidates, whatever the earlier kernels took, so candidate lists are independent of each other:
+// tokens, whatever the earlier kernels took, so the candidate sets are independent of each other and
+// are built for all kernel sizes at once:
 //
-//   pool_hist    all kernels at once: pooled score per token (sliding max by doubling, in LDS) and a
-//                4096-bin histogram of the top 12 bits of its order-preserving key
-//   find_bin     per kernel: the histogram bin in which the K_j-th largest key lies
-//   collect      all kernels at once: keys above that bin go to the candidate list, keys inside it to
-//                a boundary list
-//   refine_sort  per kernel, one workgroup: radix-select (8 bits a pass, survivors compacted) the
-//                boundary list down to what is still needed, then bitonic-sort the candidates in LDS
-//   walk         one workgroup: kernels in order, first B_j candidates not yet allocated (LDS hash
-//                set), then the allocated set sorted ascending
+//   sel_init     clears histograms and counters
+//   pool_hist<1> one workgroup per (4096-token chunk, kernel size): scores + halo into LDS, sliding
+//                maximum by doubling, a 2048-bin LDS histogram of the top 11 bits of the pooled
+//                score's order-preserving key, added to the kernel's global histogram.  The last workgroup to finish
+//                locates, per kernel, the bin holding the K_j-th largest key.
+//   pool_hist<2> same pooling; histogram of the next 11 bits of the keys inside that bin; the last
+//                workgroup locates the 22-bit prefix of the K_j-th largest key.
+//   collect      keys above the prefix go to the kernel's candidate list, keys that share it to a
+//                boundary list (a few dozen on real scores; everything on all-equal scores)
+//   refine       per kernel: a boundary list longer than kSelSmall is radix-selected down (8 bits a
+//                pass, survivors compacted) to what is needed; the rest joins the candidates
+//   allocate     one workgroup walks the kernels in order: candidates not yet allocated (LDS hash
+//                set), exact radix select of the B_j largest among them in registers, then the
+//                allocated set sorted ascending.
 //
 // Ranking is (pooled score descending, token index ascending): the 64-bit key is the ordered score
 // bits above the complemented index, so all keys are distinct and every step is order-independent;
@@ -24,9 +30,12 @@ namespace ilre {
 namespace {
 
 constexpr int kThreads = 1024;
-constexpr int kPerThread = kSelChunk / kThreads;  // 4
+constexpr int kPoolThreads = kThreads;
+constexpr int kPerThread = kSelChunk / kPoolThreads;  // 4
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kHashSlots = 16384;                 // >= 2 * ILRE_MAX_BUDGET
+constexpr int kKeysPerThread = kCandCap / kThreads;
+constexpr int kBuckets = 4096;                       // final counting sort (3 * kBuckets <= kHashSlots)
 
 struct SelParams {
     int n;
@@ -49,6 +58,11 @@ __device__ __forceinline__ uint64_t make_key(float pooled, uint32_t token)
 }
 
 __device__ __forceinline__ uint32_t key_token(uint64_t key) { return 0xFFFFFFFFu - (uint32_t)key; }
+
+__device__ __forceinline__ uint32_t load_u32(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Inclusive prefix sum over the 1024 threads of the block; wsum is 16 words of LDS scratch.
 // Every thread also receives the block total.  Contains two barriers.
@@ -74,8 +88,38 @@ __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t x, uint32_t *w
     return x + before;
 }
 
+__device__ __forceinline__ int pow2_floor(int w)
+{
+    int p = 1;
+    while (2 * p <= w) p *= 2;
+    return p;
+}
+
+__global__ __launch_bounds__(kThreads) void sel_init(const SelParams prm, uint32_t *hist, SelCtrl *ctrl, uint32_t *done)
+{
+    const int j = blockIdx.x;
+    // hist holds [2][n][kSelBins]; block j clears its rows of both levels
+    for (int i = threadIdx.x; i < kSelBins; i += kThreads) {
+        hist[(size_t)j * kSelBins + i] = 0;
+        hist[((size_t)prm.n + j) * kSelBins + i] = 0;
+    }
+    if (threadIdx.x == 0) {
+        SelCtrl c{};
+        c.want = prm.want[j];
+        c.share = prm.share[j];
+        c.radius = prm.radius[j];
+        c.bin1 = kSelBins;
+        c.bin2 = kSelBins;
+        ctrl[j] = c;
+        if (j == 0) {
+            done[0] = 0;
+            done[1] = 0;
+        }
+    }
+}
+
 // Pooled scores of this thread's kPerThread tokens of chunk `chunk` for window radius r:
-// pooled[t] = max(score[u] : |u - t| <= r, 0 <= u < L)   (MaxPooling step of Algorithm 1, stride 1,
+// pooled[t] = max(score[u] : |u - t| <= r, 0 <= u < L)   (MaxPooling step of Algorithm 1 at stride 1,
 // window clipped to the context).  b0/b1 are LDS arrays of kSelChunk + 2r floats.  Sliding maximum
 // by doubling: m_p[i] = max(score[i .. i+p-1]) for p = 1, 2, 4, ... <= w, then two overlapping
 // windows of length p cover the window of length w = 2r + 1.
@@ -84,7 +128,7 @@ __device__ __forceinline__ void pooled_chunk(const float *scores, int64_t L, int
 {
     const int len = kSelChunk + 2 * r;
     const int64_t first = chunk * kSelChunk - r;
-    for (int i = threadIdx.x; i < len; i += kThreads) {
+    for (int i = threadIdx.x; i < len; i += kPoolThreads) {
         const int64_t tok = first + i;
         b0[i] = (tok >= 0 && tok < L) ? scores[tok] : -INFINITY;
     }
@@ -93,7 +137,7 @@ __device__ __forceinline__ void pooled_chunk(const float *scores, int64_t L, int
     int p = 1;
     float *src = b0, *dst = b1;
     while (2 * p <= w) {
-        for (int i = threadIdx.x; i < len; i += kThreads) dst[i] = (i + p < len) ? fmaxf(src[i], src[i + p]) : src[i];
+        for (int i = threadIdx.x; i < len; i += kPoolThreads) dst[i] = (i + p < len) ? fmaxf(src[i], src[i + p]) : src[i];
         __syncthreads();
         float *t = src;
         src = dst;
@@ -102,79 +146,100 @@ __device__ __forceinline__ void pooled_chunk(const float *scores, int64_t L, int
     }
 #pragma unroll
     for (int k = 0; k < kPerThread; ++k) {
-        const int tl = threadIdx.x + k * kThreads;
+        const int tl = threadIdx.x + k * kPoolThreads;
         out[k] = fmaxf(src[tl], src[tl + w - p]);
     }
 }
 
-__global__ __launch_bounds__(kThreads) void sel_init(const SelParams prm, uint32_t *hist, SelCtrl *ctrl)
+// Per kernel of the list: the bin b with  count(bins > b) < need <= count(bins >= b).  One wavefront
+// per kernel (lane l scans 32 bins, descending), no block barriers.  LEVEL 1 reads `want`, LEVEL 2
+// the remainder left by level 1.
+template <int LEVEL>
+__device__ void find_bins(const uint32_t *hist, SelCtrl *ctrl, int n)
 {
-    const int j = blockIdx.x;
-    for (int i = threadIdx.x; i < kSelBins; i += kThreads) hist[(size_t)j * kSelBins + i] = 0;
-    if (threadIdx.x == 0) {
-        SelCtrl c{};
-        c.want = prm.want[j];
-        c.share = prm.share[j];
-        c.radius = prm.radius[j];
-        c.bin = kSelBins;
-        ctrl[j] = c;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void pool_hist(const float *scores, int64_t L, const SelCtrl *ctrl, uint32_t *hist)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int j = blockIdx.y;
-    const int r = (int)ctrl[j].radius;
-    uint32_t *lh = (uint32_t *)smem;
-    float *b0 = (float *)(smem + kSelBins * sizeof(uint32_t));
-    float *b1 = b0 + kSelChunk + 2 * r;
-    for (int i = threadIdx.x; i < kSelBins; i += kThreads) lh[i] = 0;
-    float pooled[kPerThread];
-    pooled_chunk(scores, L, blockIdx.x, r, b0, b1, pooled);  // has barriers: lh is cleared for all
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int BPL = kSelBins / 64;
+    for (int j = wave; j < n; j += kPoolThreads / 64) {
+        const uint32_t need = LEVEL == 1 ? ctrl[j].want : ctrl[j].need1;
+        if (need == 0 || (LEVEL == 2 && ctrl[j].bin1 >= (uint32_t)kSelBins)) continue;  // uniform in the wave
+        uint32_t sum = 0;
+#pragma unroll 8
+        for (int k = 0; k < BPL; ++k) sum += load_u32(&hist[(size_t)j * kSelBins + (kSelBins - 1 - (lane * BPL + k))]);
+        uint32_t incl = sum;
 #pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
-        const int64_t tok = (int64_t)blockIdx.x * kSelChunk + threadIdx.x + k * kThreads;
-        if (tok < L) atomicAdd(&lh[ordered_bits(pooled[k]) >> 20], 1u);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < kSelBins; i += kThreads) {
-        const uint32_t c = lh[i];
-        if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
-    }
-}
-
-// Bin b with  count(bins > b) < want <= count(bins >= b).
-__global__ __launch_bounds__(kThreads) void find_bin(const uint32_t *hist, SelCtrl *ctrl)
-{
-    __shared__ uint32_t wsum[kThreads / 64];
-    const int j = blockIdx.x;
-    const uint32_t want = ctrl[j].want;
-    if (want == 0) return;  // ctrl.bin stays out of range: nothing is collected
-    // thread i owns the 4 bins  top-4i, top-4i-1, ...  (top = kSelBins - 1), i.e. descending order
-    uint32_t own[kPerThread], sum = 0;
-#pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
-        own[k] = hist[(size_t)j * kSelBins + (kSelBins - 1 - (threadIdx.x * kPerThread + k))];
-        sum += own[k];
-    }
-    uint32_t total;
-    const uint32_t incl = block_scan_inclusive(sum, wsum, total);
-    uint32_t above = incl - sum;
-    if (above < want && want <= incl) {
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            if (above < want && want <= above + own[k]) {
-                ctrl[j].bin = kSelBins - 1 - (threadIdx.x * kPerThread + k);
-                ctrl[j].above = above;
-                ctrl[j].need = want - above;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
+        }
+        uint32_t above = incl - sum;
+        if (above < need && need <= incl) {  // one lane per kernel walks its 32 bins again
+#pragma unroll 1
+            for (int k = 0; k < BPL; ++k) {
+                const uint32_t bin = kSelBins - 1 - (lane * BPL + k);
+                const uint32_t own = load_u32(&hist[(size_t)j * kSelBins + bin]);
+                if (above < need && need <= above + own) {
+                    if (LEVEL == 1) {
+                        ctrl[j].bin1 = bin;
+                        ctrl[j].above1 = above;
+                        ctrl[j].need1 = need - above;
+                    } else {
+                        ctrl[j].bin2 = bin;
+                        ctrl[j].above2 = above;
+                        ctrl[j].need2 = need - above;
+                    }
+                }
+                above += own;
             }
-            above += own[k];
         }
     }
 }
 
-// Append the selected items of the block to a global list: one slot reservation per wavefront.
+// LEVEL 1: histogram of key bits 31..21 over all tokens.  LEVEL 2: of bits 20..10 over the tokens
+// whose bits 31..21 equal the kernel's level-1 bin.  grid = (chunks, kernel sizes).
+template <int LEVEL>
+__global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
+                                                          uint32_t *hist_all, uint32_t *done)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t lh[kSelBins];
+    __shared__ uint32_t is_last;
+    const int j = blockIdx.y, n = prm.n;
+    const int r = (int)prm.radius[j];
+    uint32_t *hist = hist_all + (size_t)(LEVEL - 1) * n * kSelBins;
+    float *b0 = (float *)smem;
+    float *b1 = b0 + kSelChunk + 2 * r;
+    const uint32_t bin1 = LEVEL == 2 ? ctrl[j].bin1 : 0;
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
+    float pooled[kPerThread];
+    pooled_chunk(scores, L, blockIdx.x, r, b0, b1, pooled);  // has barriers: lh is cleared for all
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const int64_t tok = (int64_t)blockIdx.x * kSelChunk + threadIdx.x + k * kPoolThreads;
+        if (tok >= L) continue;
+        const uint32_t key = ordered_bits(pooled[k]);
+        if (LEVEL == 1)
+            atomicAdd(&lh[key >> 21], 1u);
+        else if ((key >> 21) == bin1)
+            atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) {
+        const uint32_t c = lh[i];
+        if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
+    }
+    // The last workgroup to get here sees every histogram complete and locates the bins.  Each thread
+    // waits until its histogram atomics have been performed, then one thread counts the workgroup in
+    // (fences here cost tens of microseconds: an agent-scope release writes the L2 back).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        is_last = __hip_atomic_fetch_add(&done[LEVEL - 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                  gridDim.x * gridDim.y - 1;
+    __syncthreads();
+    if (is_last) find_bins<LEVEL>(hist, ctrl, n);
+}
+
+// Append the selected items of a wavefront to a list: one slot reservation per wavefront.
 __device__ __forceinline__ void wave_append(bool pred, uint64_t key, uint64_t *list, uint32_t *counter)
 {
     const uint64_t mask = __ballot(pred);
@@ -187,72 +252,51 @@ __device__ __forceinline__ void wave_append(bool pred, uint64_t key, uint64_t *l
     if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
 }
 
-__global__ __launch_bounds__(kThreads) void collect(const float *scores, int64_t L, SelCtrl *ctrl, uint64_t *cand,
-                                                    uint64_t *tie)
+__global__ __launch_bounds__(kPoolThreads) void collect(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
+                                                        uint64_t *cand, uint64_t *tie)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int j = blockIdx.y;
-    const int r = (int)ctrl[j].radius;
-    const uint32_t bin = ctrl[j].bin;
-    if (bin >= (uint32_t)kSelBins) return;
+    const int r = (int)prm.radius[j];
+    const uint32_t bin1 = ctrl[j].bin1, bin2 = ctrl[j].bin2;
+    if (bin1 >= (uint32_t)kSelBins || bin2 >= (uint32_t)kSelBins) return;  // nothing wanted from this kernel
+    const uint32_t prefix = (bin1 << 11) | bin2;  // 22-bit prefix of the K_j-th largest key
     float *b0 = (float *)smem;
     float *b1 = b0 + kSelChunk + 2 * r;
     float pooled[kPerThread];
     pooled_chunk(scores, L, blockIdx.x, r, b0, b1, pooled);
-    uint64_t *cand_j = cand + (size_t)j * kSortCap;
+    uint64_t *cand_j = cand + (size_t)j * kCandCap;
     uint64_t *tie_j = tie + (size_t)j * 2 * (size_t)L;
 #pragma unroll
     for (int k = 0; k < kPerThread; ++k) {
-        const int64_t tok = (int64_t)blockIdx.x * kSelChunk + threadIdx.x + k * kThreads;
+        const int64_t tok = (int64_t)blockIdx.x * kSelChunk + threadIdx.x + k * kPoolThreads;
         const bool valid = tok < L;
-        const uint32_t b = valid ? ordered_bits(pooled[k]) >> 20 : 0;
+        const uint32_t p22 = valid ? ordered_bits(pooled[k]) >> 10 : 0;
         const uint64_t key = make_key(pooled[k], (uint32_t)tok);
-        wave_append(valid && b > bin, key, cand_j, &ctrl[j].cand_n);
-        wave_append(valid && b == bin, key, tie_j, &ctrl[j].tie_n);
+        wave_append(valid && p22 > prefix, key, cand_j, &ctrl[j].cand_n);
+        wave_append(valid && p22 == prefix, key, tie_j, &ctrl[j].tie_n);
     }
 }
 
-// In-LDS bitonic sort, descending, of n (power of two) 64-bit keys by the whole block.
-__device__ void bitonic_desc(uint64_t *s, int n)
+// Boundary list -> candidates.  Short lists (the normal case) are appended whole: candidates below
+// the cut are harmless, they rank last.  Long ones are radix-selected down first.
+__global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand, uint64_t *tie, int64_t L)
 {
-    for (int k = 2; k <= n; k <<= 1) {
-        for (int jj = k >> 1; jj > 0; jj >>= 1) {
-            for (int i = threadIdx.x; i < n; i += kThreads) {
-                const int o = i ^ jj;
-                if (o > i) {
-                    const uint64_t x = s[i], y = s[o];
-                    const bool down = (i & k) == 0;
-                    if (down ? (x < y) : (x > y)) {
-                        s[i] = y;
-                        s[o] = x;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void refine_sort(SelCtrl *ctrl, uint64_t *cand, uint64_t *tie, int64_t L)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint64_t *sortbuf = (uint64_t *)smem;  // kSortCap keys
     __shared__ uint32_t h[256];
     __shared__ uint32_t cnt[2];
     __shared__ uint32_t pick[3];  // digit, count above it, count in it
 
     const int j = blockIdx.x;
-    uint64_t *cand_j = cand + (size_t)j * kSortCap;
+    uint64_t *cand_j = cand + (size_t)j * kCandCap;
     uint64_t *A = tie + (size_t)j * 2 * (size_t)L;
     uint64_t *B = A + L;
     uint32_t nA = ctrl[j].tie_n;
-    uint32_t need = ctrl[j].need;
+    uint32_t need = ctrl[j].need2;
     uint32_t candn = ctrl[j].cand_n;
     const int lane = threadIdx.x & 63;
 
-    // The boundary list shares its top 12 key bits.  Peel 8 more bits a pass until few enough
-    // survive (extra candidates below the cut are harmless: they rank last) or all are needed.
-    for (int shift = 48; shift >= 0 && nA > (uint32_t)kSelSmall && need < nA; shift -= 8) {
+    // The list shares its top 22 key bits (key64 bits 63..42).  Peel 8 more bits a pass.
+    for (int shift = 40; shift >= 0 && nA > (uint32_t)kSelSmall && need < nA; shift -= 8) {
         if (threadIdx.x < 256) h[threadIdx.x] = 0;
         if (threadIdx.x < 2) cnt[threadIdx.x] = 0;
         __syncthreads();
@@ -305,64 +349,181 @@ __global__ __launch_bounds__(kThreads) void refine_sort(SelCtrl *ctrl, uint64_t 
         A = B;
         B = t;
     }
-    // what is left of the boundary list joins the candidates
     for (uint32_t i = threadIdx.x; i < nA; i += kThreads) cand_j[candn + i] = A[i];
-    candn += nA;
-    __threadfence();
-    __syncthreads();
-
-    int n2 = 1;
-    while (n2 < (int)candn) n2 <<= 1;
-    for (int i = threadIdx.x; i < n2; i += kThreads) sortbuf[i] = i < (int)candn ? cand_j[i] : 0ull;
-    __syncthreads();
-    bitonic_desc(sortbuf, n2);
-    for (int i = threadIdx.x; i < (int)candn; i += kThreads) cand_j[i] = sortbuf[i];
-    if (threadIdx.x == 0) ctrl[j].sorted_n = candn;
+    if (threadIdx.x == 0) ctrl[j].total_n = candn + nA;
 }
 
 __device__ __forceinline__ uint32_t hash_slot(uint32_t token) { return (token * 0x9E3779B1u) >> 18; }
 
-__global__ __launch_bounds__(kThreads) void walk(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out,
-                                                 int32_t *out_idx)
+// Algorithm 1's walk: kernels in the order given; from kernel j's candidates the B_j largest keys
+// whose tokens are not yet allocated; finally the allocated set in ascending order.
+__global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out,
+                                                     int bucket_shift, int32_t *out_idx)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t *table = (uint32_t *)smem;                                  // kHashSlots
-    uint64_t *sel = (uint64_t *)(smem + kHashSlots * sizeof(uint32_t));  // ILRE_MAX_BUDGET keys for the final sort
+    uint32_t *table = (uint32_t *)smem;  // kHashSlots
+    uint32_t *sel = table + kHashSlots;  // ILRE_MAX_BUDGET tokens, then as many again for the final sort
     __shared__ uint32_t wsum[kThreads / 64];
+    __shared__ uint64_t red[2][3][kThreads / 64];  // per-wave (count, and, or), two generations
+    __shared__ uint32_t h[3][256];                 // digit histograms, three generations
+    __shared__ uint32_t nsel_ctr;
 
     for (int i = threadIdx.x; i < kHashSlots; i += kThreads) table[i] = kEmpty;
+    if (threadIdx.x < 256) h[0][threadIdx.x] = h[1][threadIdx.x] = h[2][threadIdx.x] = 0;
+    if (threadIdx.x == 0) nsel_ctr = 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    uint64_t key[kKeysPerThread];
+    auto fetch = [&](int j, uint64_t(&dst)[kKeysPerThread]) {
+        const uint32_t cn = j < n ? ctrl[j].total_n : 0;
+        const uint64_t *cand_j = cand + (size_t)(j < n ? j : 0) * kCandCap;
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k) {
+            const uint32_t i = threadIdx.x + k * kThreads;
+            dst[k] = i < cn ? cand_j[i] : 0;  // 0 is below every real key
+        }
+    };
     __syncthreads();
 
     uint32_t nsel = 0;
+    int gen = 0, hgen = 0;  // generations of red[] and h[], advanced uniformly
     for (int j = 0; j < n; ++j) {
-        const uint32_t cn = ctrl[j].sorted_n;
-        const uint32_t share = ctrl[j].share;
-        const uint64_t *cand_j = cand + (size_t)j * kSortCap;
-        uint32_t taken = 0;
-        for (uint32_t base = 0; base < cn && taken < share && nsel < (uint32_t)n_out; base += kThreads) {
-            const uint32_t i = base + threadIdx.x;
-            const bool valid = i < cn;
-            const uint32_t token = valid ? key_token(cand_j[i]) : 0;
-            bool free_tok = valid;
-            if (valid) {
-                uint32_t s = hash_slot(token);
-                while (true) {
-                    const uint32_t t = table[s];
-                    if (t == kEmpty) break;
-                    if (t == token) {
-                        free_tok = false;
-                        break;
-                    }
-                    s = (s + 1) & (kHashSlots - 1);
+        uint32_t share = ctrl[j].share;
+        if ((uint32_t)n_out - nsel < share) share = (uint32_t)n_out - nsel;
+        if (share == 0) continue;  // uniform
+        fetch(j, key);
+
+        // which of this thread's candidates are still free
+        uint32_t free_mask = 0, nfree = 0;
+        uint64_t vand = ~0ull, vor = 0;
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k) {
+            if (key[k] == 0) continue;
+            const uint32_t token = key_token(key[k]);
+            uint32_t s = hash_slot(token);
+            bool taken = false;
+            while (true) {
+                const uint32_t t = table[s];
+                if (t == kEmpty) break;
+                if (t == token) {
+                    taken = true;
+                    break;
                 }
+                s = (s + 1) & (kHashSlots - 1);
             }
-            uint32_t total;
-            const uint32_t rank = block_scan_inclusive(free_tok ? 1u : 0u, wsum, total) - (free_tok ? 1u : 0u);
-            uint32_t room = share - taken;
-            if ((uint32_t)n_out - nsel < room) room = (uint32_t)n_out - nsel;
-            if (free_tok && rank < room) {
-                // descending order of the final bitonic sort = ascending token: key is the complement
-                sel[nsel + rank] = (uint64_t)(0xFFFFFFFFu - token);
+            if (!taken) {
+                free_mask |= 1u << k;
+                ++nfree;
+                vand &= key[k];
+                vor |= key[k];
+            }
+        }
+        // block-wide count, AND and OR of the free keys: one exchange through LDS
+        uint64_t c64 = nfree;
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            c64 += __shfl_xor(c64, d);
+            vand &= __shfl_xor(vand, d);
+            vor |= __shfl_xor(vor, d);
+        }
+        if (lane == 0) {
+            red[gen][0][wave] = c64;
+            red[gen][1][wave] = vand;
+            red[gen][2][wave] = vor;
+        }
+        __syncthreads();
+        uint64_t total_free = 0, all_and = ~0ull, all_or = 0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) {
+            total_free += red[gen][0][w];
+            all_and &= red[gen][1][w];
+            all_or |= red[gen][2][w];
+        }
+        gen ^= 1;
+        const uint32_t take = share < (uint32_t)total_free ? share : (uint32_t)total_free;
+        if (take == 0) continue;  // uniform
+
+        // threshold: the take-th largest free key.  Radix select, 8 bits a pass, from the highest bit
+        // in which the free keys differ; keys are distinct, so it ends with exactly `take` keys at or
+        // above the threshold.  One barrier per pass: every wavefront locates the digit itself, and the
+        // histogram two generations back is cleared while the current one fills.
+        uint64_t thr = 0;
+        if (take < (uint32_t)total_free) {
+            const uint64_t diff = all_and ^ all_or;  // != 0: at least two distinct keys
+            int shift = 63 - __clzll((long long)diff) - 7;
+            if (shift < 0) shift = 0;
+            uint64_t pmask = shift + 8 >= 64 ? 0ull : ~0ull << (shift + 8);
+            uint64_t prefix = all_and & pmask;
+            uint32_t need = take;
+            while (true) {
+                uint32_t *hc = h[hgen];
+                if (threadIdx.x < 256) h[(hgen + 1) % 3][threadIdx.x] = 0;
+#pragma unroll
+                for (int k = 0; k < kKeysPerThread; ++k)
+                    if (((free_mask >> k) & 1u) && (key[k] & pmask) == prefix) atomicAdd(&hc[(key[k] >> shift) & 255u], 1u);
+                __syncthreads();
+                // lane l owns digits 255-4l .. 252-4l (descending)
+                uint32_t own[4], sum = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    own[k] = hc[255 - (lane * 4 + k)];
+                    sum += own[k];
+                }
+                uint32_t incl = sum;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const uint32_t y = __shfl_up(incl, d);
+                    if (lane >= d) incl += y;
+                }
+                uint32_t above = incl - sum;
+                uint32_t found = 0;  // digit | inside << 8 (inside <= kCandCap) ; above kept separately
+                uint32_t found_above = 0;
+                if (above < need && need <= incl) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if (above < need && need <= above + own[k]) {
+                            found = (255u - (lane * 4 + k)) | (own[k] << 8) | 0x80000000u;
+                            found_above = above;
+                        }
+                        above += own[k];
+                    }
+                }
+                const uint64_t who = __ballot(found != 0);
+                const int src_lane = __ffsll((unsigned long long)who) - 1;
+                found = __shfl(found, src_lane);
+                found_above = __shfl(found_above, src_lane);
+                const uint32_t digit = found & 255u, inside = (found >> 8) & 0x7FFFFFu;
+                hgen = (hgen + 1) % 3;
+                prefix |= (uint64_t)digit << shift;
+                pmask |= 255ull << shift;
+                need -= found_above;
+                if (need == inside || shift == 0) break;  // the whole digit bin is taken
+                shift = shift >= 8 ? shift - 8 : 0;       // the last digit may overlap the one before: harmless
+            }
+            thr = prefix;
+            // leave the generation after the last one used clean for the next kernel
+        }
+
+        // take every free key >= thr: one slot reservation per wavefront
+        uint32_t take_mask = 0;
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k)
+            if (((free_mask >> k) & 1u) && key[k] >= thr) take_mask |= 1u << k;
+        const uint32_t mine = (uint32_t)__popc(take_mask);
+        uint32_t incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
+        }
+        uint32_t base = 0;
+        if (lane == 63 && incl) base = atomicAdd(&nsel_ctr, incl);
+        uint32_t pos = __shfl(base, 63) + incl - mine;
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k) {
+            if ((take_mask >> k) & 1u) {
+                const uint32_t token = key_token(key[k]);
+                sel[pos++] = token;
                 uint32_t s = hash_slot(token);
                 while (true) {
                     const uint32_t old = atomicCAS(&table[s], kEmpty, token);
@@ -370,20 +531,56 @@ __global__ __launch_bounds__(kThreads) void walk(const SelCtrl *ctrl, const uint
                     s = (s + 1) & (kHashSlots - 1);
                 }
             }
-            const uint32_t got = total < room ? total : room;
-            taken += got;
-            nsel += got;
-            __syncthreads();
+        }
+        __syncthreads();
+        nsel = nsel_ctr;
+    }
+    __syncthreads();
+
+    // Ascending order of the nsel allocated tokens: counting sort on the high bits (kBuckets buckets),
+    // then each token's rank inside its bucket by counting the smaller ones.  Deterministic whatever
+    // order the tokens arrived in.
+    uint32_t *cnt = table;                  // the hash set is no longer needed
+    uint32_t *start = table + kBuckets;
+    uint32_t *fill = table + 2 * kBuckets;
+    uint32_t *grp = sel + ILRE_MAX_BUDGET;
+    for (int i = threadIdx.x; i < kBuckets; i += kThreads) {
+        cnt[i] = 0;
+        fill[i] = 0;
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nsel; i += kThreads) atomicAdd(&cnt[sel[i] >> bucket_shift], 1u);
+    __syncthreads();
+    {
+        constexpr int BPT = kBuckets / kThreads;
+        uint32_t own[BPT], sum = 0;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            own[k] = cnt[threadIdx.x * BPT + k];
+            sum += own[k];
+        }
+        uint32_t total;
+        uint32_t run = block_scan_inclusive(sum, wsum, total) - sum;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            start[threadIdx.x * BPT + k] = run;
+            run += own[k];
         }
     }
-
-    int n2 = 1;
-    while (n2 < (int)nsel) n2 <<= 1;
-    for (int i = nsel + threadIdx.x; i < n2; i += kThreads) sel[i] = 0ull;
     __syncthreads();
-    bitonic_desc(sel, n2);
-    for (int i = threadIdx.x; i < n_out; i += kThreads)
-        out_idx[i] = i < (int)nsel ? (int32_t)(0xFFFFFFFFu - (uint32_t)sel[i]) : -1;
+    for (uint32_t i = threadIdx.x; i < nsel; i += kThreads) {
+        const uint32_t t = sel[i], bkt = t >> bucket_shift;
+        grp[start[bkt] + atomicAdd(&fill[bkt], 1u)] = t;
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nsel; i += kThreads) {
+        const uint32_t t = grp[i], bkt = t >> bucket_shift;
+        const uint32_t s0 = start[bkt], s1 = s0 + cnt[bkt];
+        uint32_t rank = s0;
+        for (uint32_t q = s0; q < s1; ++q) rank += grp[q] < t ? 1u : 0u;
+        out_idx[rank] = (int32_t)t;
+    }
+    for (int i = nsel + threadIdx.x; i < n_out; i += kThreads) out_idx[i] = -1;
 }
 
 }  // namespace
@@ -394,11 +591,13 @@ SelectLayout make_select_layout(int64_t L, int n_kernels)
     SelectLayout lay{};
     size_t off = 0;
     lay.hist = off;
-    off = up(off + (size_t)n_kernels * kSelBins * sizeof(uint32_t));
+    off = up(off + 2 * (size_t)n_kernels * kSelBins * sizeof(uint32_t));
     lay.ctrl = off;
     off = up(off + (size_t)n_kernels * sizeof(SelCtrl));
+    lay.done = off;
+    off = up(off + 2 * sizeof(uint32_t));
     lay.cand = off;
-    off = up(off + (size_t)n_kernels * kSortCap * sizeof(uint64_t));
+    off = up(off + (size_t)n_kernels * kCandCap * sizeof(uint64_t));
     lay.tie = off;
     off = up(off + (size_t)n_kernels * 2 * (size_t)L * sizeof(uint64_t));
     lay.total = off;
@@ -426,27 +625,28 @@ hipError_t launch_select(const float *scores, int64_t L, int budget, const int32
     unsigned char *ws = (unsigned char *)workspace;
     uint32_t *hist = (uint32_t *)(ws + lay.hist);
     SelCtrl *ctrl = (SelCtrl *)(ws + lay.ctrl);
+    uint32_t *done = (uint32_t *)(ws + lay.done);
     uint64_t *cand = (uint64_t *)(ws + lay.cand);
     uint64_t *tie = (uint64_t *)(ws + lay.tie);
     const unsigned nchunks = (unsigned)((L + kSelChunk - 1) / kSelChunk);
-    const int n_out = (int)(budget < L ? budget : L);
+        const int n_out = (int)(budget < L ? budget : L);
     const size_t pool_lds = 2 * (size_t)(kSelChunk + 2 * rmax) * sizeof(float);
-    const size_t hist_lds = pool_lds + kSelBins * sizeof(uint32_t);
-    const size_t sort_lds = (size_t)kSortCap * sizeof(uint64_t);
-    const size_t walk_lds = kHashSlots * sizeof(uint32_t) + (size_t)ILRE_MAX_BUDGET * sizeof(uint64_t);
+        const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + 2 * (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
+    int bucket_shift = 0;
+    while (((int64_t)kBuckets << bucket_shift) < L) ++bucket_shift;
 
     hipError_t e;
-    if ((e = hipFuncSetAttribute((const void *)pool_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hist_lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)pool_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)refine_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sort_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)walk_lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)allocate, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
 
-    hipLaunchKernelGGL(sel_init, dim3(n_kernels), dim3(kThreads), 0, s, prm, hist, ctrl);
-    hipLaunchKernelGGL(pool_hist, dim3(nchunks, n_kernels), dim3(kThreads), hist_lds, s, scores, L, ctrl, hist);
-    hipLaunchKernelGGL(find_bin, dim3(n_kernels), dim3(kThreads), 0, s, hist, ctrl);
-    hipLaunchKernelGGL(collect, dim3(nchunks, n_kernels), dim3(kThreads), pool_lds, s, scores, L, ctrl, cand, tie);
-    hipLaunchKernelGGL(refine_sort, dim3(n_kernels), dim3(kThreads), sort_lds, s, ctrl, cand, tie, L);
-    hipLaunchKernelGGL(walk, dim3(1), dim3(kThreads), walk_lds, s, ctrl, cand, n_kernels, n_out, out_idx);
+    hipLaunchKernelGGL(sel_init, dim3(n_kernels), dim3(kThreads), 0, s, prm, hist, ctrl, done);
+    hipLaunchKernelGGL(pool_hist<1>, dim3(nchunks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done);
+    hipLaunchKernelGGL(pool_hist<2>, dim3(nchunks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done);
+    hipLaunchKernelGGL(collect, dim3(nchunks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, cand, tie);
+    hipLaunchKernelGGL(refine, dim3(n_kernels), dim3(kThreads), 0, s, ctrl, cand, tie, L);
+    hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n_kernels, n_out, bucket_shift, out_idx);
     return hipGetLastError();
 }
 

@@ -79,6 +79,9 @@ SELECT_CASES = [
     ("needle_like", 100000, (1, 3, 7, 15, 31), 4096, "needles"),
     ("dense_background_ties", 200000, (3, 7, 15, 31), 4096, "narrow"),
     ("max_budget", 40000, (3, 31), 8192, "random"),
+    ("twelve_kernels_two_groups", 30000, (1, 3, 5, 7, 9, 11, 13, 15, 31, 63, 127, 3), 3000, "needles"),
+    ("all_equal_large", 300000, (3, 7, 15, 31), 4096, "equal"),
+    ("two_values_heavy_ties", 150000, (1, 7), 5000, "two_values"),
 ]
 
 
@@ -87,6 +90,8 @@ def _scores_for(kind, L, rng):
         return rng.random(L).astype(np.float32)
     if kind == "few_values":
         return (rng.integers(1, 9, size=L) / 16.0).astype(np.float32)
+    if kind == "two_values":
+        return np.where(rng.random(L) < 0.01, 0.5, 0.25).astype(np.float32)
     if kind == "equal":
         return np.full(L, 0.125, dtype=np.float32)
     if kind == "narrow":   # a dense background inside one binade, as real scores are
