@@ -51,6 +51,11 @@ typedef enum {
 typedef enum { ILRE_F32 = 0, ILRE_BF16 = 1 } ilre_dtype;
 typedef enum { ILRE_SCORE_SUM = 0, ILRE_SCORE_MAX = 1 } ilre_score_mode;
 
+/* ilre_row_stats / ilre_recall: follow the running row maximum over the whole context, so that the
+   reference written to row_ref is exactly max_t logit (a few percent slower).  Without it the
+   reference is a maximum over part of the context, which normalises just as well. */
+#define ILRE_FLAG_EXACT_ROW_MAX 1
+
 #define ILRE_HEAD_DIM 128        /* the only supported head dimension */
 #define ILRE_MAX_BUDGET 8192     /* largest budget when budget < L (budget >= L needs L <= 8192) */
 #define ILRE_MAX_POOL_KERNEL 2047 /* largest pooling kernel size */
@@ -62,7 +67,7 @@ typedef struct {
     int32_t n_pool_kernels;  /* length of pool_kernels (selection entry points) */
     int32_t score_mode;      /* ilre_score_mode */
     float scale;             /* softmax scale; 0 means 1/sqrt(d) */
-    int32_t reserved;
+    int32_t flags;           /* ILRE_FLAG_* bits */
     int64_t k_stride_head;   /* elements between kv heads of k_cache;  0 = contiguous [Hkv, L, d] */
     int64_t k_stride_token;  /* elements between tokens of k_cache;    0 = contiguous */
     int64_t q_stride_head;   /* elements between heads of q;           0 = contiguous [Hq, Lq, d] */
@@ -88,18 +93,22 @@ int ilre_recall(const void *q, const void *k_cache,
                 int32_t budget, const int32_t *pool_kernels,
                 int32_t *out_idx, float *out_scores, const ilre_opts *opts);
 
-/* Stage 1 (Eq. 4 row statistics): for every row r = h*Lq + i
-   row_max[r] = max_t logit, row_sumexp[r] = sum_t exp(logit - row_max[r]); both dev, Hq*Lq float. */
+/* Stage 1 (Eq. 4 row statistics): for every row r = h*Lq + i a reference logit and the sum of
+   exponentials against it, i.e. the softmax normaliser in two parts:
+       row_sumexp[r] = sum_t exp(logit[r,t] - row_ref[r]),   log sum_t exp(logit[r,t]) = row_ref[r] + log row_sumexp[r].
+   row_ref[r] <= max_t logit[r,t]; it equals the maximum with ILRE_FLAG_EXACT_ROW_MAX, otherwise it is
+   the maximum over the first tokens of the row's context splits (row_sumexp stays finite: rows whose
+   sums would leave the fp32 range are redone against the exact maximum).  Both dev, Hq*Lq float. */
 int ilre_row_stats(const void *q, const void *k_cache,
                    int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
-                   float *row_max, float *row_sumexp, const ilre_opts *opts);
+                   float *row_ref, float *row_sumexp, const ilre_opts *opts);
 
 /* Stage 2 (Eq. 4 normalised, Eq. 5): recompute the logits, normalise with the given row
-   statistics and reduce over heads and queries.  row_max,row_sumexp: dev, as written by
-   ilre_row_stats.  out_scores: dev, L float. */
+   statistics (any pair with the right row_ref + log row_sumexp) and reduce over heads and queries.
+   row_ref,row_sumexp: dev, as written by ilre_row_stats.  out_scores: dev, L float. */
 int ilre_col_scores(const void *q, const void *k_cache,
                     int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
-                    const float *row_max, const float *row_sumexp,
+                    const float *row_ref, const float *row_sumexp,
                     float *out_scores, const ilre_opts *opts);
 
 /* Stages 3-4 (Algorithm 1): pooling, budgeted top-k with skip-allocated, ascending output.

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libilre.so")
 ILRE_OK, ILRE_EINVAL, ILRE_EUNSUPPORTED, ILRE_ENOMEM, ILRE_EHIP = range(5)
 ILRE_F32, ILRE_BF16 = 0, 1
 ILRE_SCORE_SUM, ILRE_SCORE_MAX = 0, 1
+ILRE_FLAG_EXACT_ROW_MAX = 1
 ILRE_MAX_BUDGET = 8192
 ILRE_MAX_POOL_KERNEL = 2047
 ILRE_MAX_POOL_KERNELS = 64
@@ -33,7 +34,7 @@ class IlreOpts(ctypes.Structure):
         ("n_pool_kernels", ctypes.c_int32),
         ("score_mode", ctypes.c_int32),
         ("scale", ctypes.c_float),
-        ("reserved", ctypes.c_int32),
+        ("flags", ctypes.c_int32),
         ("k_stride_head", ctypes.c_int64),
         ("k_stride_token", ctypes.c_int64),
         ("q_stride_head", ctypes.c_int64),
@@ -118,13 +119,14 @@ def _qk_meta(q: torch.Tensor, k: torch.Tensor):
 
 
 def _opts(dtype: int, n_pool_kernels: int, scale: float, score_mode: int, workspace: Optional[torch.Tensor],
-          q: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None) -> IlreOpts:
+          q: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, flags: int = 0) -> IlreOpts:
     o = IlreOpts()
     o.struct_size = ctypes.sizeof(IlreOpts)
     o.dtype = dtype
     o.n_pool_kernels = n_pool_kernels
     o.score_mode = score_mode
     o.scale = float(scale)
+    o.flags = int(flags)
     if q is not None:
         o.q_stride_head, o.q_stride_token = q.stride(0), q.stride(1)
     if k is not None:
@@ -147,7 +149,8 @@ def _kernel_array(pool_kernels: Sequence[int]):
 
 
 def ilre_recall(q: torch.Tensor, k_cache: torch.Tensor, budget: int, pool_kernels: Sequence[int], *,
-                scale: float = 0.0, score_mode: int = ILRE_SCORE_SUM, workspace: Optional[torch.Tensor] = None,
+                scale: float = 0.0, score_mode: int = ILRE_SCORE_SUM, flags: int = 0,
+                workspace: Optional[torch.Tensor] = None,
                 out_idx: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None
                 ) -> Tuple[torch.Tensor, torch.Tensor]:
     """Whole path; returns (out_idx int32[min(budget, L)] ascending, out_scores float32[L])."""
@@ -160,22 +163,23 @@ def ilre_recall(q: torch.Tensor, k_cache: torch.Tensor, budget: int, pool_kernel
         out_idx = torch.empty(min(int(budget), L), dtype=torch.int32, device=q.device)
     if out_scores is None:
         out_scores = torch.empty(L, dtype=torch.float32, device=q.device)
-    o = _opts(dt, n, scale, score_mode, workspace, q, k_cache)
+    o = _opts(dt, n, scale, score_mode, workspace, q, k_cache, flags)
     _check(load().ilre_recall(q.data_ptr(), k_cache.data_ptr(), L, Lq, Hq, Hkv, d, int(budget), _kernel_array(pool_kernels),
                               out_idx.data_ptr(), out_scores.data_ptr(), ctypes.byref(o)))
     return out_idx, out_scores
 
 
-def ilre_row_stats(q: torch.Tensor, k_cache: torch.Tensor, *, scale: float = 0.0,
+def ilre_row_stats(q: torch.Tensor, k_cache: torch.Tensor, *, scale: float = 0.0, flags: int = 0,
                    workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Softmax row maximum and sum of exponentials for every row r = h*Lq + i (float32[Hq*Lq] each)."""
+    """Softmax row reference (the row maximum with ILRE_FLAG_EXACT_ROW_MAX) and sum of exponentials
+    against it for every row r = h*Lq + i (float32[Hq*Lq] each)."""
     L, Lq, Hq, Hkv, d = _qk_meta(q, k_cache)
     dt = _dtype_code(q)
     if workspace is None:
         workspace = alloc_workspace(L, Lq, Hq, Hkv, d, 0, dt, q.device)
     row_max = torch.empty(Hq * Lq, dtype=torch.float32, device=q.device)
     row_sumexp = torch.empty(Hq * Lq, dtype=torch.float32, device=q.device)
-    o = _opts(dt, 0, scale, ILRE_SCORE_SUM, workspace, q, k_cache)
+    o = _opts(dt, 0, scale, ILRE_SCORE_SUM, workspace, q, k_cache, flags)
     _check(load().ilre_row_stats(q.data_ptr(), k_cache.data_ptr(), L, Lq, Hq, Hkv, d, row_max.data_ptr(),
                                  row_sumexp.data_ptr(), ctypes.byref(o)))
     return row_max, row_sumexp

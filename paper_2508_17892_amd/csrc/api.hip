@@ -24,7 +24,7 @@ int fail(int status, const char *fmt, ...)
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t part_m, part_z, row_max, row_sumexp, partial, select, total;
+    size_t part_m, part_z, flag, row_max, row_sumexp, partial, select, total;
     ilre::SelectLayout sel;
 };
 
@@ -36,6 +36,8 @@ Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, int n_ker
     off = up256(off + (size_t)p.nsplit * nrows * sizeof(float));
     l.part_z = off;
     off = up256(off + (size_t)p.nsplit * nrows * sizeof(float));
+    l.flag = off;
+    off = up256(off + sizeof(uint32_t));
     l.row_max = off;
     off = up256(off + (size_t)nrows * sizeof(float));
     l.row_sumexp = off;
@@ -86,6 +88,7 @@ int check_opts(const ilre_opts *o)
     if (o->score_mode != ILRE_SCORE_SUM && o->score_mode != ILRE_SCORE_MAX)
         return fail(ILRE_EUNSUPPORTED, "unknown score_mode %d", o->score_mode);
     if (!(o->scale >= 0.f) || isinf(o->scale)) return fail(ILRE_EINVAL, "scale must be finite and >= 0 (0 = 1/sqrt(d))");
+    if (o->flags & ~ILRE_FLAG_EXACT_ROW_MAX) return fail(ILRE_EUNSUPPORTED, "unknown flag bits 0x%x", o->flags);
     return ILRE_OK;
 }
 
@@ -125,6 +128,7 @@ int fill_qk(ilre::ScoreArgs &a, const void *q, const void *k, int64_t L, int32_t
     if (((uintptr_t)q & 15) || ((uintptr_t)k & 15)) return fail(ILRE_EINVAL, "q and k_cache must be 16-byte aligned");
     const float scale = o->scale > 0.f ? o->scale : 1.0f / sqrtf((float)d);
     a.c = scale * 1.4426950408889634f;
+    a.force_online = (o->flags & ILRE_FLAG_EXACT_ROW_MAX) ? 1 : 0;
     return ILRE_OK;
 }
 
@@ -171,13 +175,14 @@ int ilre_row_stats(const void *q, const void *k_cache, int64_t L, int32_t Lq, in
     const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
     const int64_t nrows = (int64_t)Hq * Lq;
     const Layout lay = make_layout(p, L, nrows, opts->n_pool_kernels > 0 ? opts->n_pool_kernels : 0);
-    if ((rc = check_workspace(opts, lay.part_z + (size_t)p.nsplit * nrows * sizeof(float)))) return rc;
+    if ((rc = check_workspace(opts, lay.row_max))) return rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
     fill_plan(a, p);
     unsigned char *ws = (unsigned char *)opts->workspace;
     a.part_m = (float *)(ws + lay.part_m);
     a.part_z = (float *)(ws + lay.part_z);
+    a.overflow = (uint32_t *)(ws + lay.flag);
     const hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
     return ILRE_OK;
@@ -243,6 +248,7 @@ int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     hipStream_t s = (hipStream_t)opts->stream;
     a.part_m = (float *)(ws + lay.part_m);
     a.part_z = (float *)(ws + lay.part_z);
+    a.overflow = (uint32_t *)(ws + lay.flag);
     float *row_max = (float *)(ws + lay.row_max);
     float *row_sumexp = (float *)(ws + lay.row_sumexp);
     hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, s);

@@ -123,6 +123,23 @@ __device__ __forceinline__ float quad_swap2(float x)  // lanes 0<->2, 1<->3 of e
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true));
 }
 
+// The same sum against a frozen reference m: no maximum, no rescale.  Any finite m gives the same
+// (m, z) pair up to rounding as long as 2^(x - m) stays in range; a row whose later logits exceed m by
+// more than ~2^7 base-2 units overflows to inf, which the caller detects and redoes with row_update.
+__device__ __forceinline__ void row_accumulate(const f32x16 &acc, float c, float m, float &z)
+{
+    const float nm = -m;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; v += 4) {
+        p0 += fast_exp2(fmaf(acc[v + 0], c, nm));
+        p1 += fast_exp2(fmaf(acc[v + 1], c, nm));
+        p2 += fast_exp2(fmaf(acc[v + 2], c, nm));
+        p3 += fast_exp2(fmaf(acc[v + 3], c, nm));
+    }
+    z += (p0 + p1) + (p2 + p3);
+}
+
 // MODE 0: row statistics.  MODE 1: column scores (RMAX = 0 sum over rows, 1 max over rows).
 template <int DT, int NB, int WAVES, int MODE, int RMAX>
 __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
@@ -157,6 +174,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     const int64_t tile0 = (int64_t)split * a.tiles_per_split;
     const int64_t tile1 = (tile0 + a.tiles_per_split < a.ntiles) ? tile0 + a.tiles_per_split : a.ntiles;
     if (tile0 >= tile1) return;
+    if (MODE == 0 && a.overflow) {
+        // the redo launch runs only if the first attempt overflowed; the first attempt clears the flag
+        if (a.force_online) {
+            if (*a.overflow == 0) return;
+        } else if (blockIdx.x == 0 && threadIdx.x == 0) {
+            *a.overflow = 0;
+        }
+    }
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -271,10 +296,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // It runs one unit behind the MFMAs, so that the matrix pipe works on unit u while the vector
     // pipe exponentiates unit u-1 from the other accumulator.
     float col = 0.f;  // pass 2: running column result of the token block over its NB query blocks
-    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, auto masked_tag, bool store) {
+    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, auto masked_tag, auto frozen_tag, bool store) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr bool FROZEN = decltype(frozen_tag)::value;
         if (MODE == 0) {
-            row_update<MASKED>(acc, a.c, m[b], z[b], tile * TN + tb * 32 + 4 * half, a.L);
+            if (FROZEN)
+                row_accumulate(acc, a.c, m[b], z[b]);
+            else
+                row_update<MASKED>(acc, a.c, m[b], z[b], tile * TN + tb * 32 + 4 * half, a.L);
         } else {
             float e[16];
 #pragma unroll
@@ -322,8 +351,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // MFMA chains are interleaved step by step; as soon as a step's fragment has fed all chains it is
     // refilled from LDS for the next block (for the last block, from the next tile's buffer).
     // CUR_RAGGED is only ever true for the last tile of the context, and only in pass 1.
-    auto do_tile = [&](int64_t tile, auto ragged_tag) {
+    auto do_tile = [&](int64_t tile, auto ragged_tag, auto frozen_tag) {
         constexpr bool CUR_RAGGED = decltype(ragged_tag)::value;
+        constexpr bool FROZEN = decltype(frozen_tag)::value;  // pass 1: reference maxima no longer move
         const int it = (int)(tile - tile0);
         if (tile + 2 < tile1) issue_tile(tile + 2, (it + 2) % 3);
         if (MODE == 1 && it >= 2) flush_columns(tile - 2);
@@ -356,9 +386,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 if (u == 0)
-                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, std::false_type{}, it > 0);
+                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, std::false_type{}, frozen_tag, it > 0);
                 else
-                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, std::bool_constant<CUR_RAGGED>{}, true);
+                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, std::bool_constant<CUR_RAGGED>{}, frozen_tag, true);
             }
             // ask the scheduler for: one MFMA (group), a slice of the vector work, and a fragment
             // read after every NB-th MFMA
@@ -381,15 +411,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // stored); the ragged tile, if any, is the last tile of the last split.
     const bool last_ragged = MODE == 0 && tile1 * TN > a.L;
     const int64_t tile_full_end = last_ragged ? tile1 - 1 : tile1;
-    for (int64_t tile = tile0; tile < tile_full_end; ++tile) do_tile(tile, std::false_type{});
-    if (last_ragged) do_tile(tile1 - 1, std::true_type{});
+    // Pass 1 follows the running maximum for the first two tiles of its split, then freezes each
+    // row's reference and only accumulates (unless the caller asked for the always-safe form).
+    int64_t online_end = tile_full_end;
+    if (MODE == 0 && !a.force_online && tile0 + 2 < tile_full_end) online_end = tile0 + 2;
+    int64_t tile = tile0;
+    for (; tile < online_end; ++tile) do_tile(tile, std::false_type{}, std::false_type{});
+    if (MODE == 0)
+        for (; tile < tile_full_end; ++tile) do_tile(tile, std::false_type{}, std::true_type{});
+    if (last_ragged) do_tile(tile1 - 1, std::true_type{}, std::false_type{});
     // drain the pipeline: the last unit of the last tile
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (last_ragged)
-            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::true_type{}, true);
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::true_type{}, std::false_type{}, true);
         else
-            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::false_type{}, true);
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::false_type{}, std::false_type{}, true);
     }
 
     if (MODE == 1) {
@@ -418,8 +455,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 // Merge the per-split partial statistics of each row (fixed split order) and convert to the
 // natural-log units of Eq. 4: row_max = max_t logit, row_sumexp = sum_t exp(logit - row_max).
 __global__ void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows, float *row_max,
-                                  float *row_sumexp)
+                                  float *row_sumexp, uint32_t *overflow, int redo)
 {
+    if (redo && *overflow == 0) return;
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= nrows) return;
     float mm = kNegBig;
@@ -428,6 +466,8 @@ __global__ void combine_row_stats(const float *part_m, const float *part_z, int 
     for (int s = 0; s < nsplit; ++s) zz += part_z[(int64_t)s * nrows + r] * fast_exp2(part_m[(int64_t)s * nrows + r] - mm);
     row_max[r] = mm * kLn2;
     row_sumexp[r] = zz;
+    // a sum that left the fp32 range under a frozen reference: ask for the safe form
+    if (overflow && !redo && !(zz <= 3.0e38f)) atomicOr(overflow, 1u);
 }
 
 // score[t] = sum (or max) over the (kv head, query block) units of their partial column results.
@@ -497,21 +537,31 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     return p;
 }
 
-hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp, hipStream_t s)
+hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a0, float *row_max, float *row_sumexp, hipStream_t s)
 {
-    hipError_t e;
+    // Attempt with frozen references, then the always-safe form, which returns at once unless the
+    // attempt raised the overflow flag.  No host synchronisation in between.
     const size_t lds = p.lds_bytes_stats;
-    if (p.dtype == ILRE_F32)
-        e = launch_score(score_kernel<ILRE_F32, 1, 4, 0, 0>, p.grid, 256, lds, a, s);
-    else if (p.waves == 4)
-        e = launch_score(score_kernel<ILRE_BF16, 2, 4, 0, 0>, p.grid, 256, lds, a, s);
-    else
-        e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
-    if (e != hipSuccess) return e;
-    const int64_t nrows = (int64_t)a.Hq * a.Lq;
-    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
-                       a.nsplit, nrows, row_max, row_sumexp);
-    return hipGetLastError();
+    const int64_t nrows = (int64_t)a0.Hq * a0.Lq;
+    // (With the exact-maximum flag the safe form is the only launch.)
+    for (int redo = a0.force_online ? 1 : 0; redo < 2; ++redo) {
+        ScoreArgs a = a0;
+        a.force_online = redo;
+        if (a0.force_online) a.overflow = nullptr;
+        hipError_t e;
+        if (p.dtype == ILRE_F32)
+            e = launch_score(score_kernel<ILRE_F32, 1, 4, 0, 0>, p.grid, 256, lds, a, s);
+        else if (p.waves == 4)
+            e = launch_score(score_kernel<ILRE_BF16, 2, 4, 0, 0>, p.grid, 256, lds, a, s);
+        else
+            e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
+                           a.nsplit, nrows, row_max, row_sumexp, a.overflow, a.overflow ? redo : 0);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s)

@@ -85,6 +85,7 @@ def test_argument_errors_need_no_device():
     assert lib.ilre_recall(fake, fake, 100000, 8, 8, 2, 128, 64, big, fake, fake, ctypes.byref(o)) == il.ILRE_EUNSUPPORTED
     assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(struct_size=8))) == il.ILRE_EINVAL
     assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(score_mode=5))) == il.ILRE_EUNSUPPORTED
+    assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(_opts(flags=64))) == il.ILRE_EUNSUPPORTED
     # undersized and misaligned workspace
     small = _opts(workspace=1 << 20, workspace_bytes=1024)
     assert lib.ilre_recall(fake, fake, 1000, 8, 8, 2, 128, 64, kern, fake, fake, ctypes.byref(small)) == il.ILRE_ENOMEM
