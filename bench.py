@@ -20,6 +20,9 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_MFMA_TFLOPS = 157.3  # fp32 matrix path (cfg 1 only)
+# HBM bytes per launch of the dominant scoring kernel, from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE
+# scaled by the 256 MiB copy (profiles/score_kernel_cfg5_1m_hbm_traffic.md); algorithmic: 2 GiB of K.
+MEASURED_TRAFFIC_BYTES = {5: {0: 3.403e9, 1: 2.232e9}}
 
 
 def main() -> int:
@@ -31,7 +34,13 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
     ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (see profiles/)")
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc; default: the figure "
+                         "recorded under profiles/ for this workload, if any")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy, the known-size kernel that scales "
+                         "FETCH_SIZE / WRITE_SIZE in rocprofv3 --pmc runs of this script")
+    ap.add_argument("--gemm-context", action="store_true",
+                    help="also time a library bf16 GEMM (8192^3, random operands) as context for the MFMA roofline")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on exactly one GPU (got --gpus {args.gpus}); "
@@ -64,6 +73,13 @@ def main() -> int:
     def step():
         il.ilre_recall(q, k, budget, kernels, workspace=ws, out_idx=out_idx, out_scores=out_scores)
 
+    if args.calib_copy:
+        cal_src = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -94,8 +110,11 @@ def main() -> int:
     dom_name = ("row_stats (score_kernel MODE 0)", "col_scores (score_kernel MODE 1)")[dom]
     achieved = flops_per_pass / (stage_ms[dom] * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
+    traffic = args.traffic_bytes
+    if traffic is None:
+        traffic = MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dom)
     roofline = {"bound": "mfma", "kernel": dom_name, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes,
+                "frac": round(achieved / peak, 4), "traffic": traffic,
                 "flops_per_launch": flops_per_pass, "launch_ms": round(stage_ms[dom], 4)}
 
     result = {
@@ -113,6 +132,21 @@ def main() -> int:
                          "col_scores": round(flops_per_pass / stage_ms[1] / 1e9, 1)},
         "roofline": roofline,
     }
+
+    if args.gemm_context:
+        n = 8192
+        ga = torch.randn(n, n, device="cuda").to(torch.bfloat16)
+        gb = torch.randn(n, n, device="cuda").to(torch.bfloat16)
+        torch.matmul(ga, gb)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            torch.matmul(ga, gb)
+        e1.record()
+        torch.cuda.synchronize()
+        result["context"] = {"library_bf16_gemm_8192_tflops": round(2.0 * n ** 3 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)}
+        del ga, gb
 
     if not args.no_cpu_baseline:
         import oracle
