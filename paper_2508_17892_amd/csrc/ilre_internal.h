@@ -60,15 +60,17 @@ hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_m
 
 // ---------------------------------------------------------------- selection (Algorithm 1)
 
-constexpr int kSelChunk = 4096;     // tokens per workgroup in the pooling passes
+constexpr int kSelFine = 256;       // tokens a wavefront pools at a time ("fine chunk")
 constexpr int kSelBins = 2048;      // histogram bins per level: 11 key bits
 constexpr int kSelSmall = 2048;     // boundary lists up to this long join the candidates unrefined
 constexpr int kCandCap = 10240;     // candidate list capacity (>= ILRE_MAX_BUDGET + kSelSmall)
 
 struct SelectLayout {
-    size_t hist;      // uint32 [2][n][kSelBins]  (level 1, level 2)
-    size_t ctrl;      // SelCtrl [n]
-    size_t done;      // uint32 [2]: workgroups finished per histogram level
+    size_t hist;      // uint32 [2][n][kSelBins]  (level 1, level 2), then [2][kSelBins] of the pre-pass
+    size_t ctrl;      // SelCtrl [n + 1]  (the last one belongs to the pre-pass)
+    size_t done;      // uint32 [2][n], then [2] of the pre-pass: workgroups finished per level and kernel
+    size_t cmax;      // float [ceil(L / kSelFine)]: fine-chunk maxima (pruning pre-pass)
+    size_t active;    // uint32 [ceil(L / kSelFine)]: fine chunks left after pruning
     size_t cand;      // uint64 [n][kCandCap]
     size_t tie;       // uint64 [n][2][L]   (ping-pong lists of boundary elements)
     size_t total;

@@ -29,9 +29,10 @@
 namespace ilre {
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kPoolThreads = kThreads;
-constexpr int kPerThread = kSelChunk / kPoolThreads;  // 4
+constexpr int kThreads = 1024;                    // refine, allocate: one large workgroup
+constexpr int kPoolThreads = 256;                 // pooling passes: four wavefronts, one fine chunk each
+constexpr int kPoolWaves = kPoolThreads / 64;
+constexpr int kPerThread = kSelFine / 64;         // 4 tokens per lane
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kHashSlots = 16384;                 // >= 2 * ILRE_MAX_BUDGET
 constexpr int kKeysPerThread = kCandCap / kThreads;
@@ -111,34 +112,48 @@ __global__ __launch_bounds__(kThreads) void sel_init(const SelParams prm, uint32
         c.bin1 = kSelBins;
         c.bin2 = kSelBins;
         ctrl[j] = c;
-        if (j == 0) {
-            done[0] = 0;
-            done[1] = 0;
-        }
+        done[j] = 0;          // [2][n]: workgroups finished per histogram level and kernel
+        done[prm.n + j] = 0;
     }
 }
 
-// Pooled scores of this thread's kPerThread tokens of chunk `chunk` for window radius r:
+// The fine chunks (kSelFine tokens) a pooling pass visits: all of them, or a list built by the
+// pruning pre-pass.
+struct Entries {
+    const uint32_t *list;    // null: entry i is fine chunk i
+    const uint32_t *list_n;  // device count of list entries
+    uint32_t nfine;          // ceil(L / kSelFine)
+};
+__device__ __forceinline__ uint32_t entry_count(const Entries &e) { return e.list ? load_u32(e.list_n) : e.nfine; }
+__device__ __forceinline__ uint32_t entry_chunk(const Entries &e, uint32_t i) { return e.list ? e.list[i] : i; }
+
+// A wavefront's LDS operations complete in order; waiting for them (and telling the compiler that
+// memory changed) is all the synchronisation a wavefront-private buffer needs.
+__device__ __forceinline__ void lds_wave_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// Pooled scores of this lane's kPerThread tokens of fine chunk `fc` for window radius r, computed by
+// one wavefront in its own LDS buffers b0/b1 (kSelFine + 2r floats each):
 // pooled[t] = max(score[u] : |u - t| <= r, 0 <= u < L)   (MaxPooling step of Algorithm 1 at stride 1,
-// window clipped to the context).  b0/b1 are LDS arrays of kSelChunk + 2r floats.  Sliding maximum
-// by doubling: m_p[i] = max(score[i .. i+p-1]) for p = 1, 2, 4, ... <= w, then two overlapping
-// windows of length p cover the window of length w = 2r + 1.
-__device__ __forceinline__ void pooled_chunk(const float *scores, int64_t L, int64_t chunk, int r, float *b0, float *b1,
-                                             float (&out)[kPerThread])
+// window clipped to the context).  Sliding maximum by doubling: m_p[i] = max(score[i .. i+p-1]) for
+// p = 1, 2, 4, ... <= w, then two overlapping windows of length p cover the window of length w = 2r+1.
+__device__ __forceinline__ void pooled_wave(const float *scores, int64_t L, int64_t fc, int r, float *b0, float *b1,
+                                            float (&out)[kPerThread])
 {
-    const int len = kSelChunk + 2 * r;
-    const int64_t first = chunk * kSelChunk - r;
-    for (int i = threadIdx.x; i < len; i += kPoolThreads) {
+    const int lane = threadIdx.x & 63;
+    const int len = kSelFine + 2 * r;
+    const int64_t first = fc * kSelFine - r;
+    lds_wave_sync();  // the previous chunk's reads of these buffers are done
+    for (int i = lane; i < len; i += 64) {
         const int64_t tok = first + i;
         b0[i] = (tok >= 0 && tok < L) ? scores[tok] : -INFINITY;
     }
-    __syncthreads();
+    lds_wave_sync();
     const int w = 2 * r + 1;
     int p = 1;
     float *src = b0, *dst = b1;
     while (2 * p <= w) {
-        for (int i = threadIdx.x; i < len; i += kPoolThreads) dst[i] = (i + p < len) ? fmaxf(src[i], src[i + p]) : src[i];
-        __syncthreads();
+        for (int i = lane; i < len; i += 64) dst[i] = (i + p < len) ? fmaxf(src[i], src[i + p]) : src[i];
+        lds_wave_sync();
         float *t = src;
         src = dst;
         dst = t;
@@ -146,22 +161,21 @@ __device__ __forceinline__ void pooled_chunk(const float *scores, int64_t L, int
     }
 #pragma unroll
     for (int k = 0; k < kPerThread; ++k) {
-        const int tl = threadIdx.x + k * kPoolThreads;
+        const int tl = lane + k * 64;
         out[k] = fmaxf(src[tl], src[tl + w - p]);
     }
 }
 
-// Per kernel of the list: the bin b with  count(bins > b) < need <= count(bins >= b).  One wavefront
-// per kernel (lane l scans 32 bins, descending), no block barriers.  LEVEL 1 reads `want`, LEVEL 2
-// the remainder left by level 1.
+// For kernel j: the bin b with  count(bins > b) < need <= count(bins >= b), by one wavefront (lane l
+// scans 32 bins, descending).  LEVEL 1 reads `want`, LEVEL 2 the remainder left by level 1.
 template <int LEVEL>
-__device__ void find_bins(const uint32_t *hist, SelCtrl *ctrl, int n)
+__device__ void find_bins(const uint32_t *hist, SelCtrl *ctrl, int j)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
     constexpr int BPL = kSelBins / 64;
-    for (int j = wave; j < n; j += kPoolThreads / 64) {
+    if (threadIdx.x < 64) {
         const uint32_t need = LEVEL == 1 ? ctrl[j].want : ctrl[j].need1;
-        if (need == 0 || (LEVEL == 2 && ctrl[j].bin1 >= (uint32_t)kSelBins)) continue;  // uniform in the wave
+        if (need == 0 || (LEVEL == 2 && ctrl[j].bin1 >= (uint32_t)kSelBins)) return;  // uniform in the wave
         uint32_t sum = 0;
 #pragma unroll 8
         for (int k = 0; k < BPL; ++k) sum += load_u32(&hist[(size_t)j * kSelBins + (kSelBins - 1 - (lane * BPL + k))]);
@@ -194,53 +208,9 @@ __device__ void find_bins(const uint32_t *hist, SelCtrl *ctrl, int n)
     }
 }
 
-// LEVEL 1: histogram of key bits 31..21 over all tokens.  LEVEL 2: of bits 20..10 over the tokens
-// whose bits 31..21 equal the kernel's level-1 bin.  grid = (chunks, kernel sizes).
-template <int LEVEL>
-__global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
-                                                          uint32_t *hist_all, uint32_t *done)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ uint32_t lh[kSelBins];
-    __shared__ uint32_t is_last;
-    const int j = blockIdx.y, n = prm.n;
-    const int r = (int)prm.radius[j];
-    uint32_t *hist = hist_all + (size_t)(LEVEL - 1) * n * kSelBins;
-    float *b0 = (float *)smem;
-    float *b1 = b0 + kSelChunk + 2 * r;
-    const uint32_t bin1 = LEVEL == 2 ? ctrl[j].bin1 : 0;
-    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
-    float pooled[kPerThread];
-    pooled_chunk(scores, L, blockIdx.x, r, b0, b1, pooled);  // has barriers: lh is cleared for all
-#pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
-        const int64_t tok = (int64_t)blockIdx.x * kSelChunk + threadIdx.x + k * kPoolThreads;
-        if (tok >= L) continue;
-        const uint32_t key = ordered_bits(pooled[k]);
-        if (LEVEL == 1)
-            atomicAdd(&lh[key >> 21], 1u);
-        else if ((key >> 21) == bin1)
-            atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) {
-        const uint32_t c = lh[i];
-        if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
-    }
-    // The last workgroup to get here sees every histogram complete and locates the bins.  Each thread
-    // waits until its histogram atomics have been performed, then one thread counts the workgroup in
-    // (fences here cost tens of microseconds: an agent-scope release writes the L2 back).
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0)
-        is_last = __hip_atomic_fetch_add(&done[LEVEL - 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                  gridDim.x * gridDim.y - 1;
-    __syncthreads();
-    if (is_last) find_bins<LEVEL>(hist, ctrl, n);
-}
-
 // Append the selected items of a wavefront to a list: one slot reservation per wavefront.
-__device__ __forceinline__ void wave_append(bool pred, uint64_t key, uint64_t *list, uint32_t *counter)
+template <typename T>
+__device__ __forceinline__ void wave_append(bool pred, T item, T *list, uint32_t *counter)
 {
     const uint64_t mask = __ballot(pred);
     if (mask == 0) return;
@@ -249,33 +219,153 @@ __device__ __forceinline__ void wave_append(bool pred, uint64_t key, uint64_t *l
     uint32_t base = 0;
     if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(mask));
     base = __shfl(base, leader);
-    if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+    if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = item;
+}
+
+// LEVEL 1: histogram of key bits 31..21 over the visited tokens.  LEVEL 2: of bits 20..10 over the
+// tokens whose bits 31..21 equal the kernel's level-1 bin.  grid = (workgroups, kernel sizes); the
+// wavefronts of the grid share out the entries.
+template <int LEVEL>
+__global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
+                                                          uint32_t *hist_all, uint32_t *done, const Entries ent)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t lh[kSelBins];
+    __shared__ uint32_t is_last;
+    const int j = blockIdx.y, n = prm.n;
+    const int r = (int)prm.radius[j];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t *hist = hist_all + (size_t)(LEVEL - 1) * n * kSelBins;
+    float *b0 = (float *)smem + (size_t)wave * 2 * (kSelFine + 2 * r);
+    float *b1 = b0 + kSelFine + 2 * r;
+    const uint32_t bin1 = LEVEL == 2 ? ctrl[j].bin1 : 0;
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
+    __syncthreads();
+    const uint32_t nent = entry_count(ent);
+    for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
+        const int64_t fc = entry_chunk(ent, e);
+        float pooled[kPerThread];
+        pooled_wave(scores, L, fc, r, b0, b1, pooled);
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int64_t tok = fc * kSelFine + lane + k * 64;
+            if (tok >= L) continue;
+            const uint32_t key = ordered_bits(pooled[k]);
+            if (LEVEL == 1)
+                atomicAdd(&lh[key >> 21], 1u);
+            else if ((key >> 21) == bin1)
+                atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) {
+        const uint32_t c = lh[i];
+        if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
+    }
+    // The last workgroup of kernel j to get here sees its histogram complete and locates the bin.  Each thread
+    // waits until its histogram atomics have been performed, then one thread counts the workgroup in
+    // (fences here cost tens of microseconds: an agent-scope release writes the L2 back).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        is_last = __hip_atomic_fetch_add(&done[(LEVEL - 1) * n + j], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                  gridDim.x - 1;
+    __syncthreads();
+    if (is_last) find_bins<LEVEL>(hist, ctrl, j);
 }
 
 __global__ __launch_bounds__(kPoolThreads) void collect(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
-                                                        uint64_t *cand, uint64_t *tie)
+                                                        uint64_t *cand, uint64_t *tie, const Entries ent)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int j = blockIdx.y;
     const int r = (int)prm.radius[j];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t bin1 = ctrl[j].bin1, bin2 = ctrl[j].bin2;
     if (bin1 >= (uint32_t)kSelBins || bin2 >= (uint32_t)kSelBins) return;  // nothing wanted from this kernel
     const uint32_t prefix = (bin1 << 11) | bin2;  // 22-bit prefix of the K_j-th largest key
-    float *b0 = (float *)smem;
-    float *b1 = b0 + kSelChunk + 2 * r;
-    float pooled[kPerThread];
-    pooled_chunk(scores, L, blockIdx.x, r, b0, b1, pooled);
+    float *b0 = (float *)smem + (size_t)wave * 2 * (kSelFine + 2 * r);
+    float *b1 = b0 + kSelFine + 2 * r;
     uint64_t *cand_j = cand + (size_t)j * kCandCap;
     uint64_t *tie_j = tie + (size_t)j * 2 * (size_t)L;
+    const uint32_t nent = entry_count(ent);
+    for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
+        const int64_t fc = entry_chunk(ent, e);
+        float pooled[kPerThread];
+        pooled_wave(scores, L, fc, r, b0, b1, pooled);
 #pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
-        const int64_t tok = (int64_t)blockIdx.x * kSelChunk + threadIdx.x + k * kPoolThreads;
-        const bool valid = tok < L;
-        const uint32_t p22 = valid ? ordered_bits(pooled[k]) >> 10 : 0;
-        const uint64_t key = make_key(pooled[k], (uint32_t)tok);
-        wave_append(valid && p22 > prefix, key, cand_j, &ctrl[j].cand_n);
-        wave_append(valid && p22 == prefix, key, tie_j, &ctrl[j].tie_n);
+        for (int k = 0; k < kPerThread; ++k) {
+            const int64_t tok = fc * kSelFine + lane + k * 64;
+            const bool valid = tok < L;
+            const uint32_t p22 = valid ? ordered_bits(pooled[k]) >> 10 : 0;
+            const uint64_t key = make_key(pooled[k], (uint32_t)tok);
+            wave_append(valid && p22 > prefix, key, cand_j, &ctrl[j].cand_n);
+            wave_append(valid && p22 == prefix, key, tie_j, &ctrl[j].tie_n);
+        }
     }
+}
+
+// Pruning pre-pass for long contexts, step 1: cm[c] = max of the scores of fine chunk c.  Pure
+// streaming; a wavefront reads four chunks (4 KiB) per iteration.
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true)));   // quad 1,0,3,2
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true)));   // quad 2,3,0,1
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, true)));  // row_half_mirror
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, true)));  // row_mirror
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+__global__ __launch_bounds__(kPoolThreads) void chunk_max(const float *scores, int64_t L, uint32_t nfine, float *cm)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t stride = gridDim.x * kPoolWaves * 4;
+    for (uint32_t c0 = (blockIdx.x * kPoolWaves + wave) * 4; c0 < nfine; c0 += stride) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t tok = (int64_t)(c0 + u) * kSelFine + lane * 4;
+            if (tok + 3 < L) {
+                v[u] = *(const float4 *)(scores + tok);
+            } else {
+                v[u].x = tok + 0 < L ? scores[tok + 0] : -INFINITY;
+                v[u].y = tok + 1 < L ? scores[tok + 1] : -INFINITY;
+                v[u].z = tok + 2 < L ? scores[tok + 2] : -INFINITY;
+                v[u].w = -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float m = wave_max(fmaxf(fmaxf(v[u].x, v[u].y), fmaxf(v[u].z, v[u].w)));
+            if (lane == 0 && c0 + u < nfine) cm[c0 + u] = m;
+        }
+    }
+}
+
+// Pruning pre-pass, step 3 (step 2 is the two-level histogram run on cm for the `budget`-th largest
+// chunk maximum): at least `budget` tokens score at or above the lower edge of that maximum's 22-bit
+// prefix, so no kernel admits a token whose pooled score is below it; a fine chunk can only hold such
+// a token if a chunk maximum within `reach` chunks of it reaches the prefix.
+__global__ __launch_bounds__(kPoolThreads) void mark_active(const float *cm, uint32_t nfine, int reach, SelCtrl *pctrl,
+                                                            uint32_t *list)
+{
+    const uint32_t c = blockIdx.x * kPoolThreads + threadIdx.x;
+    const uint32_t bin1 = pctrl->bin1, bin2 = pctrl->bin2;
+    const uint32_t prefix = (bin1 >= (uint32_t)kSelBins || bin2 >= (uint32_t)kSelBins) ? 0u : (bin1 << 11) | bin2;
+    bool active = false;
+    if (c < nfine) {
+        float m = cm[c];
+        for (int d = 1; d <= reach; ++d) {
+            if (c >= (uint32_t)d) m = fmaxf(m, cm[c - d]);
+            if (c + d < nfine) m = fmaxf(m, cm[c + d]);
+        }
+        active = (ordered_bits(m) >> 10) >= prefix;
+    }
+    wave_append(active, c, list, &pctrl->cand_n);
 }
 
 // Boundary list -> candidates.  Short lists (the normal case) are appended whole: candidates below
@@ -589,13 +679,18 @@ SelectLayout make_select_layout(int64_t L, int n_kernels)
 {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     SelectLayout lay{};
+    const size_t nfine = (size_t)((L + kSelFine - 1) / kSelFine);
     size_t off = 0;
     lay.hist = off;
-    off = up(off + 2 * (size_t)n_kernels * kSelBins * sizeof(uint32_t));
+    off = up(off + 2 * (size_t)(n_kernels + 1) * kSelBins * sizeof(uint32_t));  // + the pre-pass's own pair
     lay.ctrl = off;
-    off = up(off + (size_t)n_kernels * sizeof(SelCtrl));
+    off = up(off + (size_t)(n_kernels + 1) * sizeof(SelCtrl));
     lay.done = off;
-    off = up(off + 2 * sizeof(uint32_t));
+    off = up(off + 2 * (size_t)(n_kernels + 1) * sizeof(uint32_t));
+    lay.cmax = off;
+    off = up(off + nfine * sizeof(float));
+    lay.active = off;
+    off = up(off + nfine * sizeof(uint32_t));
     lay.cand = off;
     off = up(off + (size_t)n_kernels * kCandCap * sizeof(uint64_t));
     lay.tie = off;
@@ -628,12 +723,20 @@ hipError_t launch_select(const float *scores, int64_t L, int budget, const int32
     uint32_t *done = (uint32_t *)(ws + lay.done);
     uint64_t *cand = (uint64_t *)(ws + lay.cand);
     uint64_t *tie = (uint64_t *)(ws + lay.tie);
-    const unsigned nchunks = (unsigned)((L + kSelChunk - 1) / kSelChunk);
-        const int n_out = (int)(budget < L ? budget : L);
-    const size_t pool_lds = 2 * (size_t)(kSelChunk + 2 * rmax) * sizeof(float);
-        const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + 2 * (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
+    const int n_out = (int)(budget < L ? budget : L);
+    const uint32_t nfine = (uint32_t)((L + kSelFine - 1) / kSelFine);
+    const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)(kSelFine + 2 * rmax) * sizeof(float);
+    const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + 2 * (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
     int bucket_shift = 0;
     while (((int64_t)kBuckets << bucket_shift) < L) ++bucket_shift;
+    // Workgroups per kernel size in the pooling passes; beyond the cap the wavefronts loop over the
+    // entries.  The histogram passes end with one atomic per hot bin and workgroup on a handful of
+    // addresses (about 13 ns each, serialised), so they use fewer, longer-running workgroups.
+    auto pool_blocks = [](uint32_t entries, uint32_t cap) {
+        const uint32_t want = (entries + kPoolWaves - 1) / kPoolWaves;
+        return want < cap ? (want ? want : 1u) : cap;
+    };
+    constexpr uint32_t kHistCap = 256, kCollectCap = 1024;
 
     hipError_t e;
     if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
@@ -641,10 +744,38 @@ hipError_t launch_select(const float *scores, int64_t L, int budget, const int32
     if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)allocate, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
 
+    Entries ent{nullptr, nullptr, nfine};
+    // Long contexts: visit only the fine chunks that can hold an admitted token.
+    if ((int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384) {
+        float *cm = (float *)(ws + lay.cmax);
+        uint32_t *active = (uint32_t *)(ws + lay.active);
+        uint32_t *phist = hist + 2 * (size_t)n_kernels * kSelBins;
+        SelCtrl *pctrl = ctrl + n_kernels;
+        uint32_t *pdone = done + 2 * (size_t)n_kernels;
+        SelParams pp{};
+        pp.n = 1;
+        pp.L = nfine;
+        pp.want[0] = (uint32_t)n_out;
+        const uint32_t nfine2 = (nfine + kSelFine - 1) / kSelFine;
+        const Entries all{nullptr, nullptr, nfine2};
+        const size_t lds0 = (size_t)kPoolWaves * 2 * kSelFine * sizeof(float);
+        hipLaunchKernelGGL(chunk_max, dim3(2048), dim3(kPoolThreads), 0, s, scores, L, nfine, cm);
+        hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, pp, phist, pctrl, pdone);
+        hipLaunchKernelGGL(pool_hist<1>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, (int64_t)nfine, pp, pctrl, phist, pdone, all);
+        hipLaunchKernelGGL(pool_hist<2>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, (int64_t)nfine, pp, pctrl, phist, pdone, all);
+        const int reach = (rmax + kSelFine - 1) / kSelFine;
+        hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, cm, nfine, reach, pctrl, active);
+        ent = Entries{active, &pctrl->cand_n, nfine};
+    }
+    // with a list the entry count is only known on the device: size the grid for the worst case the
+    // pruning rule is meant for (a few times the budget) and let the wavefronts loop
+    const uint32_t entries = ent.list ? 4u * (uint32_t)n_out + 1024u : nfine;
+    const uint32_t hblocks = pool_blocks(entries, kHistCap), cblocks = pool_blocks(entries, kCollectCap);
+
     hipLaunchKernelGGL(sel_init, dim3(n_kernels), dim3(kThreads), 0, s, prm, hist, ctrl, done);
-    hipLaunchKernelGGL(pool_hist<1>, dim3(nchunks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done);
-    hipLaunchKernelGGL(pool_hist<2>, dim3(nchunks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done);
-    hipLaunchKernelGGL(collect, dim3(nchunks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, cand, tie);
+    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(collect, dim3(cblocks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, cand, tie, ent);
     hipLaunchKernelGGL(refine, dim3(n_kernels), dim3(kThreads), 0, s, ctrl, cand, tie, L);
     hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n_kernels, n_out, bucket_shift, out_idx);
     return hipGetLastError();
