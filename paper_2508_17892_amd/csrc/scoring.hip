@@ -155,6 +155,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     constexpr int TBLOCKS = TN / 32;
     constexpr int UNITS = TBLOCKS;              // pipeline units per tile: one per 32-token block
     constexpr int NPART = WAVES * 2;            // partial column results per token (pass 2)
+    constexpr int RSTR = TN + 36;               // row pitch of the partial-result buffers: keeps the two
+                                                // half-waves' stores and the flush's four lane groups on
+                                                // different LDS banks
     static_assert(TN * CPR % (64 * WAVES) == 0, "tile must divide over the wavefronts");
     static_assert(UNITS % 2 == 0, "units alternate between two accumulators");
     static_assert(TN == 16 * WAVES && NPART % 4 == 0, "column flush: 16 tokens per wavefront, 4 lanes per token");
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     float m[NB], z[NB];
     // pass-2 state: per accumulator register the row's exponent offset -(max*log2e + log2 sum)
     float noff[MODE == 1 ? NB : 1][16];
-    float *red = (float *)(smem + 3 * TILE_BYTES);  // [3][NPART][TN], pass 2 only
+    float *red = (float *)(smem + 3 * TILE_BYTES);  // [3][NPART][RSTR], pass 2 only
     const int unit = g * a.nqb + qb;
 
     if (MODE == 0) {
@@ -276,12 +279,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // Pass 2: combine the NPART partial column results of a finished tile in a fixed order.  Wave w
     // takes tokens 16w..16w+15, four lanes per token, each lane NPART/4 partials, then the quad.
     auto flush_columns = [&](int64_t tile) {
-        const float *rb = red + (int)((tile - tile0) % 3) * NPART * TN;
+        const float *rb = red + (int)((tile - tile0) % 3) * NPART * RSTR;
         const int tl = wave * 16 + (lane >> 2), part0 = (lane & 3) * (NPART / 4);
-        float acc = rb[part0 * TN + tl];
+        float acc = rb[part0 * RSTR + tl];
 #pragma unroll
         for (int k = 1; k < NPART / 4; ++k) {
-            const float x = rb[(part0 + k) * TN + tl];
+            const float x = rb[(part0 + k) * RSTR + tl];
             acc = RMAX ? fmaxf(acc, x) : acc + x;
         }
         const float x1 = quad_swap1(acc);
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
             else
                 col = RMAX ? fmaxf(col, part) : col + part;
             if (b == NB - 1 && store)
-                red[((int)((tile - tile0) % 3) * NPART + wave * 2 + half) * TN + tb * 32 + l32] = col;
+                red[((int)((tile - tile0) % 3) * NPART + wave * 2 + half) * RSTR + tb * 32 + l32] = col;
         }
     };
 
@@ -398,7 +401,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
                 for (int b = 0; b < NB; ++b) {
                     __builtin_amdgcn_sched_group_barrier(0x008, DT == ILRE_BF16 ? 1 : STEPS / 2, 0);
                     if (b == NB - 1) __builtin_amdgcn_sched_group_barrier(0x100, STEPS / 8, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, MODE == 0 ? 8 : 6, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, (MODE == 0 && !FROZEN) ? 8 : 6, 0);
                 }
             }
         }
@@ -533,7 +536,7 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     p.grid = (int)(((pairs + kNumXCD - 1) / kNumXCD) * kNumXCD * p.nqb);
     const size_t tiles = dtype == ILRE_F32 ? tile_lds_bytes<ILRE_F32>(p.waves) : tile_lds_bytes<ILRE_BF16>(p.waves);
     p.lds_bytes_stats = tiles;
-    p.lds_bytes_cols = tiles + 3 * 2 * (size_t)p.waves * p.tile_tokens * sizeof(float);
+    p.lds_bytes_cols = tiles + 3 * 2 * (size_t)p.waves * (p.tile_tokens + 36) * sizeof(float);
     return p;
 }
 

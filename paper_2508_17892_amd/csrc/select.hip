@@ -7,10 +7,11 @@
 // are built for all kernel sizes at once:
 //
 //   sel_init     clears histograms and counters
-//   pool_hist<1> one workgroup per (4096-token chunk, kernel size): scores + halo into LDS, sliding
-//                maximum by doubling, a 2048-bin LDS histogram of the top 11 bits of the pooled
-//                score's order-preserving key, added to the kernel's global histogram.  The last workgroup to finish
-//                locates, per kernel, the bin holding the K_j-th largest key.
+//   pool_hist<1> wavefronts share out the 256-token "fine chunks": scores + halo into the wavefront's
+//                own LDS buffers, sliding maximum by doubling (no block barriers), a 2048-bin LDS
+//                histogram of the top 11 bits of the pooled score's order-preserving key, added to the
+//                kernel's global histogram.  The last workgroup of a kernel size to finish locates
+//                the bin holding its K_j-th largest key.
 //   pool_hist<2> same pooling; histogram of the next 11 bits of the keys inside that bin; the last
 //                workgroup locates the 22-bit prefix of the K_j-th largest key.
 //   collect      keys above the prefix go to the kernel's candidate list, keys that share it to a
@@ -20,6 +21,11 @@
 //   allocate     one workgroup walks the kernels in order: candidates not yet allocated (LDS hash
 //                set), exact radix select of the B_j largest among them in registers, then the
 //                allocated set sorted ascending.
+//
+// Long contexts (L >= 4M and >= 1024 tokens per budgeted token) start with a pruning pre-pass: the
+// maximum of every fine chunk (one streaming read of the scores), the 22-bit prefix of the budget-th
+// largest of those maxima (the same two histogram passes, run on the maxima), and the list of fine
+// chunks that can still hold an admitted token; the three pooling passes then visit only that list.
 //
 // Ranking is (pooled score descending, token index ascending): the 64-bit key is the ordered score
 // bits above the complemented index, so all keys are distinct and every step is order-independent;
