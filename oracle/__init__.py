@@ -7,7 +7,8 @@ from __future__ import annotations
 
 import numpy as np
 
-from .allocation import allocate, max_pool_same, split_budget, thresholds
+from .allocation import (allocate, allocate_max_avg, avg_pool_same, max_pool_same, max_pool_strided, split_budget,
+                         thresholds)
 from .scoring import MODE_MAX, MODE_SUM, num_threads, row_stats, scores
 
 
@@ -19,5 +20,5 @@ def recall(q, k, pool_kernels, budget, scale=None, mode=MODE_SUM):
     return idx, score
 
 
-__all__ = ["allocate", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
+__all__ = ["allocate", "allocate_max_avg", "avg_pool_same", "max_pool_strided", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
            "num_threads", "recall", "MODE_SUM", "MODE_MAX"]

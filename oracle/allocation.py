@@ -85,3 +85,78 @@ def thresholds(score: np.ndarray, pool_kernels: Sequence[int], budget: int):
         allocated[take] = True
         out.append((pooled, float(pooled[take[-1]]) if take.size else None))
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Algorithm 1 as printed: strided max pooling, then stride-1 average pooling, one combination per
+# (max kernel, average kernel) pair.
+#
+# Readings taken where the algorithm is silent:
+#   * MaxPooling(size = stride = m) keeps floor(L/m) whole cells; the up to m-1 tokens after the last
+#     whole cell are never candidates of that max kernel;
+#   * AvgPooling(size = n, stride 1) returns one value per cell: the window of cell p is
+#     [p - floor((n-1)/2), p + floor(n/2)], cells outside the array count as zero, and the sum is
+#     divided by n.  The sum is taken in the array's own precision, left to right;
+#   * "Select top K_m indices": K_m = floor(B/m) + 1 cells, ranked (value descending, cell ascending);
+#   * "Map back": cell p stands for its m tokens p*m .. p*m+m-1, walked in ascending order;
+#   * B_c = floor(B / (N_M*N_A)), the first B mod (N_M*N_A) combinations taking one more; a combination
+#     stops early when its K_m cells are used up, so fewer than B tokens may come out;
+#   * combinations run with the max kernel in the outer loop and the average kernel in the inner loop;
+#   * sink part: the first `sink` tokens are always allocated and take no part in the pooling (the
+#     scores handed to the pooling are score[sink:]); the budget B counts the other tokens.
+
+
+def max_pool_strided(score: np.ndarray, m: int) -> np.ndarray:
+    """cell[p] = max(score[p*m : p*m+m]) for the floor(L/m) whole cells (MaxPooling, size = stride = m)."""
+    if m < 1:
+        raise ValueError("max kernel must be >= 1")
+    cells = score.shape[0] // m
+    return score[:cells * m].reshape(cells, m).max(axis=1) if cells else score[:0].copy()
+
+
+def avg_pool_same(x: np.ndarray, n: int) -> np.ndarray:
+    """out[p] = (x[p-a] + ... + x[p+b]) / n with a = (n-1)//2, b = n//2, zeros outside, summed left to
+    right in x's dtype (AvgPooling, size n, stride 1)."""
+    if n < 1:
+        raise ValueError("average kernel must be >= 1")
+    Lc = x.shape[0]
+    acc = np.zeros(Lc, dtype=x.dtype)
+    for off in range(-((n - 1) // 2), n // 2 + 1):
+        lo, hi = max(0, -off), min(Lc, Lc - off)       # cells p with 0 <= p + off < Lc
+        if lo < hi:
+            acc[lo:hi] = acc[lo:hi] + x[lo + off:hi + off]
+    return acc / x.dtype.type(n)
+
+
+def allocate_max_avg(score: np.ndarray, max_kernels: Sequence[int], avg_kernels: Sequence[int], budget: int,
+                     sink: int = 0) -> np.ndarray:
+    """Algorithm 1 with strided max pooling and average pooling; returns I sorted ascending (int64),
+    the sink indices included."""
+    L = score.shape[0]
+    if sink < 0 or sink > L:
+        raise ValueError("sink out of range")
+    body = score[sink:]
+    Lb = body.shape[0]
+    shares = split_budget(budget, len(max_kernels) * len(avg_kernels))
+    allocated = np.zeros(Lb, dtype=bool)
+    combo = 0
+    for m in max_kernels:
+        m = int(m)
+        cells = max_pool_strided(body, m)
+        k_m = budget // m + 1
+        cell_id = np.arange(cells.shape[0])
+        for n in avg_kernels:
+            pooled = avg_pool_same(cells, int(n))
+            order = np.lexsort((cell_id, -pooled.astype(np.float64)))[:k_m]
+            added = 0
+            for p in order:
+                if added >= shares[combo]:
+                    break
+                for t in range(p * m, p * m + m):
+                    if added >= shares[combo]:
+                        break
+                    if not allocated[t]:
+                        allocated[t] = True
+                        added += 1
+            combo += 1
+    return np.concatenate([np.arange(sink), sink + np.flatnonzero(allocated)]).astype(np.int64)

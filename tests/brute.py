@@ -53,3 +53,35 @@ def brute_allocate(score, kernels, budget):
                 chosen.add(t)
                 got += 1
     return sorted(chosen)
+
+
+def brute_allocate_max_avg(score, max_kernels, avg_kernels, budget, sink=0):
+    """Algorithm 1 with strided max pooling then average pooling, cell by cell, on numpy float32 scalars
+    (the precision the decisions are taken in).  Same readings as the oracle states."""
+    import numpy as np
+    body = [np.float32(x) for x in score[sink:]]
+    Lb = len(body)
+    ncombo = len(max_kernels) * len(avg_kernels)
+    shares = [budget // ncombo + (1 if c < budget % ncombo else 0) for c in range(ncombo)]
+    chosen = set()
+    combo = 0
+    for m in max_kernels:
+        ncell = Lb // m
+        cells = [max(body[p * m:p * m + m]) for p in range(ncell)]
+        k_m = budget // m + 1
+        for n in avg_kernels:
+            pooled = []
+            for p in range(ncell):
+                acc = np.float32(0)
+                for q in range(p - (n - 1) // 2, p + n // 2 + 1):
+                    acc = np.float32(acc + (cells[q] if 0 <= q < ncell else np.float32(0)))
+                pooled.append(np.float32(acc / np.float32(n)))
+            ranked = sorted(range(ncell), key=lambda p: (-float(pooled[p]), p))[:k_m]
+            added = 0
+            for p in ranked:
+                for t in range(p * m, p * m + m):
+                    if added < shares[combo] and t not in chosen:
+                        chosen.add(t)
+                        added += 1
+            combo += 1
+    return list(range(sink)) + [sink + t for t in sorted(chosen)]

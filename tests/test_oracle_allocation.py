@@ -99,3 +99,71 @@ def test_thresholds_replay():
     assert (pooled3 == oracle.max_pool_same(s, 3)).all()
     # every token strictly above a kernel's threshold in its pooled vector is allocated by then
     assert set(np.flatnonzero(pooled3 > thr3)).issubset(set(idx.tolist()))
+
+
+# ---- Algorithm 1 as printed: strided max pooling then average pooling ---------------------------
+
+from brute import brute_allocate_max_avg  # noqa: E402
+
+
+def test_golden_max_avg_examples(golden_dir):
+    with open(os.path.join(golden_dir, "allocation_worked.json")) as f:
+        cases = json.load(f)["max_avg_cases"]
+    for c in cases:
+        got = oracle.allocate_max_avg(np.array(c["score"], dtype=np.float32), c["max_kernels"], c["avg_kernels"],
+                                      c["budget"], sink=c["sink"])
+        assert got.tolist() == c["expect"], c["name"]
+
+
+@pytest.mark.parametrize("m", [1, 2, 4, 8])
+def test_strided_max_matches_library(m):
+    rng = np.random.default_rng(m)
+    s = rng.random(203).astype(np.float32)
+    lib = torch.nn.functional.max_pool1d(torch.from_numpy(s)[None, None, :], kernel_size=m, stride=m)[0, 0].numpy()
+    assert oracle.max_pool_strided(s, m).tolist() == lib.tolist()
+
+
+@pytest.mark.parametrize("n", list(range(1, 17)))
+def test_avg_pool_matches_library_up_to_rounding_and_index_shift(n):
+    rng = np.random.default_rng(100 + n)
+    x = rng.random(77).astype(np.float32)
+    got = oracle.avg_pool_same(x, n)
+    # torch pads n//2 zeros on both sides and counts them: its output q averages [q - n//2, q + (n-1)//2 ... ],
+    # i.e. for even n the same windows shifted by one cell
+    lib = torch.nn.functional.avg_pool1d(torch.from_numpy(x)[None, None, :], kernel_size=n, stride=1, padding=n // 2,
+                                         count_include_pad=True)[0, 0].numpy()
+    lib = lib[1:] if n % 2 == 0 else lib
+    np.testing.assert_allclose(got, lib[:77], rtol=2e-6, atol=1e-7)
+    # and exactly the float32 left-to-right definition
+    for p in (0, 1, 38, 76):
+        acc = np.float32(0)
+        for q in range(p - (n - 1) // 2, p + n // 2 + 1):
+            acc = np.float32(acc + (x[q] if 0 <= q < 77 else np.float32(0)))
+        assert got[p] == np.float32(acc / np.float32(n))
+
+
+def test_kernel_one_max_and_avg_is_plain_topk_with_cap():
+    rng = np.random.default_rng(3)
+    s = rng.random(300).astype(np.float32)
+    got = oracle.allocate_max_avg(s, [1], [1], 40)
+    want = np.sort(np.argsort(-s, kind="stable")[:40])
+    assert got.tolist() == want.tolist()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_brute_force_max_avg(seed):
+    rng = np.random.default_rng(200 + seed)
+    L = int(rng.integers(9, 90))
+    s = (rng.integers(0, 12, size=L) / 16.0 + 0.0625).astype(np.float32) if seed % 2 else rng.random(L).astype(np.float32)
+    mk = [int(x) for x in rng.choice([1, 2, 4, 8], size=int(rng.integers(1, 4)), replace=False)]
+    ak = [int(x) for x in rng.choice(np.arange(1, 9), size=int(rng.integers(1, 4)), replace=False)]
+    B = int(rng.integers(1, L + 3))
+    sink = int(rng.integers(0, 4))
+    assert oracle.allocate_max_avg(s, mk, ak, B, sink=sink).tolist() == brute_allocate_max_avg(s.tolist(), mk, ak, B, sink)
+
+
+def test_max_avg_structure():
+    rng = np.random.default_rng(9)
+    s = rng.random(5000).astype(np.float32)
+    idx = oracle.allocate_max_avg(s, [2, 4, 8], list(range(1, 17)), 480, sink=4)
+    assert idx[:4].tolist() == [0, 1, 2, 3] and (np.diff(idx) > 0).all() and len(idx) <= 4 + 480 and idx.max() < 5000
