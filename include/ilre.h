@@ -15,6 +15,17 @@
  *                        0 <= u < L); among tokens not yet allocated take the B_j with the largest
  *                        pooled_j (ties: lower index first); B_j = floor(B/n) (+1 for the first
  *                        B mod n kernels); finally the allocated set sorted ascending.
+ *   Section 3.2, Algorithm 1 as printed (the *_max_avg entry points): the first `sink` tokens are
+ *                        always allocated and the pooling sees body = score[sink..L).  For each max
+ *                        kernel m_i (outer loop) and average kernel n_j (inner loop):
+ *                        cell[p] = max(body[p*m_i .. p*m_i+m_i-1]) for the floor(len/m_i) whole cells;
+ *                        avg[p] = (cell[p-a] + ... + cell[p+b]) / n_j, a = (n_j-1)/2, b = n_j/2 (integer
+ *                        division), zeros outside the array, summed left to right in fp32; the
+ *                        K_m = B/m_i + 1 cells with the largest avg (ties: lower cell first) are the
+ *                        candidates, walked in that order, each as its m_i tokens in ascending order,
+ *                        and the first B_c tokens not yet allocated are taken, B_c = floor(B/(N_M N_A))
+ *                        (+1 for the first B mod (N_M N_A) combinations).  A combination whose
+ *                        candidates run out takes fewer, so fewer than B tokens may come back.
  *
  * Conventions for every entry point
  *   - returns an ilre_status; never throws, never aborts, never synchronises the device;
@@ -59,7 +70,9 @@ typedef enum { ILRE_SCORE_SUM = 0, ILRE_SCORE_MAX = 1 } ilre_score_mode;
 #define ILRE_HEAD_DIM 128        /* the only supported head dimension */
 #define ILRE_MAX_BUDGET 8192     /* largest budget when budget < L (budget >= L needs L <= 8192) */
 #define ILRE_MAX_POOL_KERNEL 2047 /* largest pooling kernel size */
-#define ILRE_MAX_POOL_KERNELS 64 /* most kernel sizes in one call */
+#define ILRE_MAX_POOL_KERNELS 64 /* most kernel sizes (or max/average combinations) in one call */
+#define ILRE_MAX_MAX_KERNEL 1024 /* largest strided max-pooling kernel (the *_max_avg entry points) */
+#define ILRE_MAX_AVG_KERNEL 1024 /* largest average-pooling kernel */
 
 typedef struct {
     int32_t struct_size;     /* sizeof(ilre_opts), for versioning */
@@ -87,7 +100,7 @@ int ilre_workspace_bytes(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t
    k_cache    dev  [Hkv, L, d] (strides in opts; token-major [L, Hkv, d] is expressible)
    pool_kernels host, opts->n_pool_kernels odd sizes >= 1, processed in this order
    out_idx    dev  min(budget, L) int32, ascending, unique
-   out_scores dev  L float, the un-pooled per-token score of Eq. 5 */
+   out_scores dev  L float, 16-byte aligned, the un-pooled per-token score of Eq. 5 */
 int ilre_recall(const void *q, const void *k_cache,
                 int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                 int32_t budget, const int32_t *pool_kernels,
@@ -112,9 +125,41 @@ int ilre_col_scores(const void *q, const void *k_cache,
                     float *out_scores, const ilre_opts *opts);
 
 /* Stages 3-4 (Algorithm 1): pooling, budgeted top-k with skip-allocated, ascending output.
-   scores: dev, L finite floats.  pool_kernels: host.  out_idx: dev, min(budget, L) int32. */
+   scores: dev, L finite floats, 16-byte aligned.  pool_kernels: host.  out_idx: dev, min(budget, L) int32. */
 int ilre_select(const float *scores, int64_t L, int32_t budget, const int32_t *pool_kernels,
                 int32_t *out_idx, const ilre_opts *opts);
+
+/* Algorithm 1 as printed (strided max pooling, stride-1 average pooling, K_m cap, sink part); see the
+   top of this file for the exact definition.  The paper's default is max kernels {2,4,8}, average
+   kernels {1..16}, sink 4.
+   scores      dev  L finite floats (all positions, the sink part included)
+   sink        leading tokens always kept, 0 <= sink <= L; budget counts the other tokens
+   max_kernels host n_max sizes in [1, ILRE_MAX_MAX_KERNEL]; avg_kernels host n_avg sizes in
+               [1, ILRE_MAX_AVG_KERNEL]; n_max * n_avg <= ILRE_MAX_POOL_KERNELS
+   out_idx     dev  sink + min(budget, L - sink) int32: the sink indices, then the allocated tokens
+               ascending, then -1 in the slots a run of exhausted candidates left unused
+   out_count   dev  one int32, the number of valid leading entries of out_idx; may be NULL
+   workspace   sized by ilre_workspace_bytes_max_avg for the same L, sink and max kernels */
+int ilre_select_max_avg(const float *scores, int64_t L, int32_t sink, int32_t budget,
+                        const int32_t *max_kernels, int32_t n_max,
+                        const int32_t *avg_kernels, int32_t n_avg,
+                        int32_t *out_idx, int32_t *out_count, const ilre_opts *opts);
+
+/* The whole path with Algorithm 1 as printed: Eq. 4 over all L positions, Eq. 5, then
+   ilre_select_max_avg on the scores.  q, k_cache, out_scores as for ilre_recall; the other arguments
+   as for ilre_select_max_avg.  opts->n_pool_kernels is not read. */
+int ilre_recall_max_avg(const void *q, const void *k_cache,
+                        int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                        int32_t sink, int32_t budget,
+                        const int32_t *max_kernels, int32_t n_max,
+                        const int32_t *avg_kernels, int32_t n_avg,
+                        int32_t *out_idx, int32_t *out_count, float *out_scores, const ilre_opts *opts);
+
+/* Workspace bytes for the two *_max_avg entry points (host computation only; the sizes of the
+   average kernels do not matter).  max_kernels, out_bytes: host. */
+int ilre_workspace_bytes_max_avg(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d, int32_t sink,
+                                 const int32_t *max_kernels, int32_t n_max, int32_t n_avg,
+                                 int32_t dtype, size_t *out_bytes);
 
 /* Message for the last non-OK status returned to the calling thread (static storage, never NULL). */
 const char *ilre_last_error(void);

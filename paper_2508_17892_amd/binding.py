@@ -22,9 +22,11 @@ ILRE_FLAG_EXACT_ROW_MAX = 1
 ILRE_MAX_BUDGET = 8192
 ILRE_MAX_POOL_KERNEL = 2047
 ILRE_MAX_POOL_KERNELS = 64
+ILRE_MAX_MAX_KERNEL = 1024
+ILRE_MAX_AVG_KERNEL = 1024
 
 EXPORTS = ("ilre_workspace_bytes", "ilre_recall", "ilre_row_stats", "ilre_col_scores", "ilre_select",
-           "ilre_last_error")
+           "ilre_select_max_avg", "ilre_recall_max_avg", "ilre_workspace_bytes_max_avg", "ilre_last_error")
 
 
 class IlreOpts(ctypes.Structure):
@@ -73,6 +75,14 @@ def load() -> ctypes.CDLL:
         lib.ilre_col_scores.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, po]
         lib.ilre_select.restype = ctypes.c_int
         lib.ilre_select.argtypes = [vp, i64, i32, ctypes.POINTER(i32), vp, po]
+        pi = ctypes.POINTER(i32)
+        lib.ilre_select_max_avg.restype = ctypes.c_int
+        lib.ilre_select_max_avg.argtypes = [vp, i64, i32, i32, pi, i32, pi, i32, vp, vp, po]
+        lib.ilre_recall_max_avg.restype = ctypes.c_int
+        lib.ilre_recall_max_avg.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, pi, i32, pi, i32, vp, vp, vp, po]
+        lib.ilre_workspace_bytes_max_avg.restype = ctypes.c_int
+        lib.ilre_workspace_bytes_max_avg.argtypes = [i64, i32, i32, i32, i32, i32, pi, i32, i32, i32,
+                                                     ctypes.POINTER(ctypes.c_size_t)]
         lib.ilre_last_error.restype = ctypes.c_char_p
         lib.ilre_last_error.argtypes = []
         _lib = lib
@@ -220,3 +230,62 @@ def ilre_select(scores: torch.Tensor, budget: int, pool_kernels: Sequence[int], 
     _check(load().ilre_select(scores.data_ptr(), L, int(budget), _kernel_array(pool_kernels), out_idx.data_ptr(),
                               ctypes.byref(o)))
     return out_idx
+
+
+def ilre_workspace_bytes_max_avg(L: int, Lq: int, Hq: int, Hkv: int, d: int, sink: int, max_kernels: Sequence[int],
+                                 n_avg: int, dtype: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().ilre_workspace_bytes_max_avg(L, Lq, Hq, Hkv, d, int(sink), _kernel_array(max_kernels), len(max_kernels),
+                                               int(n_avg), dtype, ctypes.byref(out)))
+    return int(out.value)
+
+
+def alloc_workspace_max_avg(L: int, Lq: int, Hq: int, Hkv: int, d: int, sink: int, max_kernels: Sequence[int], n_avg: int,
+                            dtype: int, device="cuda") -> torch.Tensor:
+    return torch.empty(ilre_workspace_bytes_max_avg(L, Lq, Hq, Hkv, d, sink, max_kernels, n_avg, dtype), dtype=torch.uint8,
+                       device=device)
+
+
+def ilre_select_max_avg(scores: torch.Tensor, budget: int, max_kernels: Sequence[int], avg_kernels: Sequence[int],
+                        sink: int = 0, *, workspace: Optional[torch.Tensor] = None, out_idx: Optional[torch.Tensor] = None,
+                        out_count: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Algorithm 1 as printed on a float32 score vector; returns (out_idx int32[sink + min(budget, L - sink)] with
+    -1 in unused slots, out_count int32[1])."""
+    if scores.dtype != torch.float32 or scores.dim() != 1 or not scores.is_contiguous() or not scores.is_cuda:
+        raise ValueError("scores must be a contiguous float32 device vector")
+    L = scores.numel()
+    if workspace is None:
+        workspace = alloc_workspace_max_avg(L, 1, 1, 1, 128, sink, max_kernels, len(avg_kernels), ILRE_F32, scores.device)
+    if out_idx is None:
+        out_idx = torch.empty(int(sink) + min(int(budget), L - int(sink)), dtype=torch.int32, device=scores.device)
+    if out_count is None:
+        out_count = torch.empty(1, dtype=torch.int32, device=scores.device)
+    o = _opts(ILRE_F32, 0, 0.0, ILRE_SCORE_SUM, workspace)
+    _check(load().ilre_select_max_avg(scores.data_ptr(), L, int(sink), int(budget), _kernel_array(max_kernels),
+                                      len(max_kernels), _kernel_array(avg_kernels), len(avg_kernels), out_idx.data_ptr(),
+                                      out_count.data_ptr(), ctypes.byref(o)))
+    return out_idx, out_count
+
+
+def ilre_recall_max_avg(q: torch.Tensor, k_cache: torch.Tensor, budget: int, max_kernels: Sequence[int],
+                        avg_kernels: Sequence[int], sink: int = 0, *, scale: float = 0.0,
+                        score_mode: int = ILRE_SCORE_SUM, flags: int = 0, workspace: Optional[torch.Tensor] = None,
+                        out_idx: Optional[torch.Tensor] = None, out_count: Optional[torch.Tensor] = None,
+                        out_scores: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Whole path with Algorithm 1 as printed; returns (out_idx, out_count, out_scores float32[L])."""
+    L, Lq, Hq, Hkv, d = _qk_meta(q, k_cache)
+    dt = _dtype_code(q)
+    if workspace is None:
+        workspace = alloc_workspace_max_avg(L, Lq, Hq, Hkv, d, sink, max_kernels, len(avg_kernels), dt, q.device)
+    if out_idx is None:
+        out_idx = torch.empty(int(sink) + min(int(budget), L - int(sink)), dtype=torch.int32, device=q.device)
+    if out_count is None:
+        out_count = torch.empty(1, dtype=torch.int32, device=q.device)
+    if out_scores is None:
+        out_scores = torch.empty(L, dtype=torch.float32, device=q.device)
+    o = _opts(dt, 0, scale, score_mode, workspace, q, k_cache, flags)
+    _check(load().ilre_recall_max_avg(q.data_ptr(), k_cache.data_ptr(), L, Lq, Hq, Hkv, d, int(sink), int(budget),
+                                      _kernel_array(max_kernels), len(max_kernels), _kernel_array(avg_kernels),
+                                      len(avg_kernels), out_idx.data_ptr(), out_count.data_ptr(), out_scores.data_ptr(),
+                                      ctypes.byref(o)))
+    return out_idx, out_count, out_scores

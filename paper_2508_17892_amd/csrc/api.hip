@@ -28,7 +28,34 @@ struct Layout {
     ilre::SelectLayout sel;
 };
 
-Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, int n_kernels)
+ilre::SelectJob window_job(int64_t L, int budget, const int32_t *pool_kernels, int n_kernels)
+{
+    ilre::SelectJob job{};
+    job.mode = ilre::kSelWindowMax;
+    job.L = L;
+    job.budget = budget;
+    job.n_max = n_kernels;
+    job.n_avg = 1;
+    job.max_kernels = pool_kernels;
+    return job;
+}
+
+ilre::SelectJob max_avg_job(int64_t L, int sink, int budget, const int32_t *max_kernels, int n_max,
+                            const int32_t *avg_kernels, int n_avg)
+{
+    ilre::SelectJob job{};
+    job.mode = ilre::kSelMaxAvg;
+    job.L = L - sink;
+    job.sink = sink;
+    job.budget = budget;
+    job.n_max = n_max;
+    job.n_avg = n_avg;
+    job.max_kernels = max_kernels;
+    job.avg_kernels = avg_kernels;
+    return job;
+}
+
+Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, const ilre::SelectJob &job)
 {
     Layout l{};
     size_t off = 0;
@@ -45,7 +72,7 @@ Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, int n_ker
     l.partial = off;
     off = up256(off + (size_t)p.nunits * (size_t)L * sizeof(float));
     l.select = off;
-    l.sel = ilre::make_select_layout(L, n_kernels > 0 ? n_kernels : 1);
+    l.sel = ilre::make_select_layout(job);
     off += l.sel.total;
     l.total = off;
     return l;
@@ -77,6 +104,35 @@ int check_kernels(int64_t L, int32_t budget, const int32_t *pool_kernels, int32_
     const int64_t n_out = budget < L ? budget : L;
     if (n_out > ILRE_MAX_BUDGET)
         return fail(ILRE_EUNSUPPORTED, "min(budget, L) = %lld over the limit %d", (long long)n_out, ILRE_MAX_BUDGET);
+    return ILRE_OK;
+}
+
+// Kernel sizes of the printed form of Algorithm 1 (the arrays may be null only when the sizes
+// themselves are not needed: n_avg sizes never are for workspace sizing).
+int check_max_avg(int64_t L, int32_t sink, int32_t budget, const int32_t *max_kernels, int32_t n_max,
+                  const int32_t *avg_kernels, int32_t n_avg, bool sizing)
+{
+    if (L < 1 || L > 0x7FFFFFFFll) return fail(ILRE_EINVAL, "L must be in [1, 2^31)");
+    if (sink < 0 || sink > L) return fail(ILRE_EINVAL, "sink must be in [0, L]");
+    if (!max_kernels || (!sizing && !avg_kernels)) return fail(ILRE_EINVAL, "max_kernels or avg_kernels is null");
+    if (n_max < 1 || n_avg < 1) return fail(ILRE_EINVAL, "n_max and n_avg must be positive");
+    if ((int64_t)n_max * n_avg > ILRE_MAX_POOL_KERNELS)
+        return fail(ILRE_EUNSUPPORTED, "more than %d pooling combinations", ILRE_MAX_POOL_KERNELS);
+    for (int i = 0; i < n_max; ++i) {
+        if (max_kernels[i] < 1) return fail(ILRE_EINVAL, "max-pooling kernel size %d must be >= 1", max_kernels[i]);
+        if (max_kernels[i] > ILRE_MAX_MAX_KERNEL)
+            return fail(ILRE_EUNSUPPORTED, "max-pooling kernel size %d over the limit %d", max_kernels[i], ILRE_MAX_MAX_KERNEL);
+    }
+    if (sizing) return ILRE_OK;
+    for (int i = 0; i < n_avg; ++i) {
+        if (avg_kernels[i] < 1) return fail(ILRE_EINVAL, "average-pooling kernel size %d must be >= 1", avg_kernels[i]);
+        if (avg_kernels[i] > ILRE_MAX_AVG_KERNEL)
+            return fail(ILRE_EUNSUPPORTED, "average-pooling kernel size %d over the limit %d", avg_kernels[i], ILRE_MAX_AVG_KERNEL);
+    }
+    if (budget < 1) return fail(ILRE_EINVAL, "budget must be positive");
+    const int64_t n_out = budget < L - sink ? budget : L - sink;
+    if (n_out > ILRE_MAX_BUDGET)
+        return fail(ILRE_EUNSUPPORTED, "min(budget, L - sink) = %lld over the limit %d", (long long)n_out, ILRE_MAX_BUDGET);
     return ILRE_OK;
 }
 
@@ -161,7 +217,20 @@ int ilre_workspace_bytes(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t
     if (n_pool_kernels < 0 || n_pool_kernels > ILRE_MAX_POOL_KERNELS)
         return fail(ILRE_EINVAL, "n_pool_kernels out of range");
     const ilre::ScorePlan p = ilre::make_score_plan(dtype, L, Lq, Hq, Hkv);
-    *out_bytes = make_layout(p, L, (int64_t)Hq * Lq, n_pool_kernels).total;
+    *out_bytes = make_layout(p, L, (int64_t)Hq * Lq, window_job(L, 1, nullptr, n_pool_kernels)).total;
+    return ILRE_OK;
+}
+
+int ilre_workspace_bytes_max_avg(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d, int32_t sink,
+                                 const int32_t *max_kernels, int32_t n_max, int32_t n_avg, int32_t dtype,
+                                 size_t *out_bytes)
+{
+    if (!out_bytes) return fail(ILRE_EINVAL, "out_bytes is null");
+    int rc = check_shape(L, Lq, Hq, Hkv, d, dtype);
+    if (rc) return rc;
+    if ((rc = check_max_avg(L, sink, 1, max_kernels, n_max, nullptr, n_avg, true))) return rc;
+    const ilre::ScorePlan p = ilre::make_score_plan(dtype, L, Lq, Hq, Hkv);
+    *out_bytes = make_layout(p, L, (int64_t)Hq * Lq, max_avg_job(L, sink, 1, max_kernels, n_max, nullptr, n_avg)).total;
     return ILRE_OK;
 }
 
@@ -174,7 +243,7 @@ int ilre_row_stats(const void *q, const void *k_cache, int64_t L, int32_t Lq, in
     if (!row_max || !row_sumexp) return fail(ILRE_EINVAL, "row_max or row_sumexp is null");
     const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
     const int64_t nrows = (int64_t)Hq * Lq;
-    const Layout lay = make_layout(p, L, nrows, opts->n_pool_kernels > 0 ? opts->n_pool_kernels : 0);
+    const Layout lay = make_layout(p, L, nrows, window_job(L, 1, nullptr, 0));
     if ((rc = check_workspace(opts, lay.row_max))) return rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
@@ -197,7 +266,7 @@ int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, i
     if (!row_max || !row_sumexp || !out_scores) return fail(ILRE_EINVAL, "row_max, row_sumexp or out_scores is null");
     const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
     const int64_t nrows = (int64_t)Hq * Lq;
-    const Layout lay = make_layout(p, L, nrows, 0);
+    const Layout lay = make_layout(p, L, nrows, window_job(L, 1, nullptr, 0));
     if ((rc = check_workspace(opts, lay.select))) return rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
@@ -218,29 +287,42 @@ int ilre_select(const float *scores, int64_t L, int32_t budget, const int32_t *p
     if (rc) return rc;
     if (L < 1 || L > 0x7FFFFFFFll) return fail(ILRE_EINVAL, "L must be in [1, 2^31)");
     if (!scores || !out_idx) return fail(ILRE_EINVAL, "scores or out_idx is null");
+    if ((uintptr_t)scores & 15) return fail(ILRE_EINVAL, "scores must be 16-byte aligned");
     if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
     // The selection region sits at the end of the workspace whatever the scoring shape was; used
     // alone it starts at the workspace base.
-    const ilre::SelectLayout sel = ilre::make_select_layout(L, opts->n_pool_kernels);
+    const ilre::SelectJob job = window_job(L, budget, pool_kernels, opts->n_pool_kernels);
+    const ilre::SelectLayout sel = ilre::make_select_layout(job);
     if ((rc = check_workspace(opts, sel.total))) return rc;
-    const hipError_t e = ilre::launch_select(scores, L, budget, pool_kernels, opts->n_pool_kernels, out_idx,
-                                             opts->workspace, sel, (hipStream_t)opts->stream);
+    const hipError_t e = ilre::launch_select(scores, job, out_idx, nullptr, opts->workspace, sel, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "selection launch");
     return ILRE_OK;
 }
 
-int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
-                int32_t budget, const int32_t *pool_kernels, int32_t *out_idx, float *out_scores, const ilre_opts *opts)
+int ilre_select_max_avg(const float *scores, int64_t L, int32_t sink, int32_t budget, const int32_t *max_kernels,
+                        int32_t n_max, const int32_t *avg_kernels, int32_t n_avg, int32_t *out_idx, int32_t *out_count,
+                        const ilre_opts *opts)
 {
     int rc = check_opts(opts);
     if (rc) return rc;
-    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
-    if (!out_idx || !out_scores) return fail(ILRE_EINVAL, "out_idx or out_scores is null");
-    if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
-    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
-    const int64_t nrows = (int64_t)Hq * Lq;
-    const Layout lay = make_layout(p, L, nrows, opts->n_pool_kernels);
-    if ((rc = check_workspace(opts, lay.total))) return rc;
+    if (!scores || !out_idx) return fail(ILRE_EINVAL, "scores or out_idx is null");
+    if ((uintptr_t)scores & 3) return fail(ILRE_EINVAL, "scores must be 4-byte aligned");
+    if ((rc = check_max_avg(L, sink, budget, max_kernels, n_max, avg_kernels, n_avg, false))) return rc;
+    const ilre::SelectJob job = max_avg_job(L, sink, budget, max_kernels, n_max, avg_kernels, n_avg);
+    const ilre::SelectLayout sel = ilre::make_select_layout(job);
+    if ((rc = check_workspace(opts, sel.total))) return rc;
+    const hipError_t e = ilre::launch_select(scores + sink, job, out_idx, out_count, opts->workspace, sel, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "selection launch");
+    return ILRE_OK;
+}
+
+namespace {
+
+// Eq. 4 and Eq. 5 into out_scores (the part the two forms of the whole path share).
+int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                float *out_scores, const ilre_opts *opts, const ilre::ScorePlan &p, const Layout &lay)
+{
+    int rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
     fill_plan(a, p);
@@ -258,7 +340,48 @@ int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     a.partial = (float *)(ws + lay.partial);
     e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s);
     if (e != hipSuccess) return hip_fail(e, "column-score launch");
-    e = ilre::launch_select(out_scores, L, budget, pool_kernels, opts->n_pool_kernels, out_idx, ws + lay.select, lay.sel, s);
+    return ILRE_OK;
+}
+
+}  // namespace
+
+int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                int32_t budget, const int32_t *pool_kernels, int32_t *out_idx, float *out_scores, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
+    if (!out_idx || !out_scores) return fail(ILRE_EINVAL, "out_idx or out_scores is null");
+    if ((uintptr_t)out_scores & 15) return fail(ILRE_EINVAL, "out_scores must be 16-byte aligned");
+    if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
+    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
+    const ilre::SelectJob job = window_job(L, budget, pool_kernels, opts->n_pool_kernels);
+    const Layout lay = make_layout(p, L, (int64_t)Hq * Lq, job);
+    if ((rc = check_workspace(opts, lay.total))) return rc;
+    if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay))) return rc;
+    unsigned char *ws = (unsigned char *)opts->workspace;
+    const hipError_t e = ilre::launch_select(out_scores, job, out_idx, nullptr, ws + lay.select, lay.sel, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "selection launch");
+    return ILRE_OK;
+}
+
+int ilre_recall_max_avg(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                        int32_t sink, int32_t budget, const int32_t *max_kernels, int32_t n_max,
+                        const int32_t *avg_kernels, int32_t n_avg, int32_t *out_idx, int32_t *out_count,
+                        float *out_scores, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
+    if (!out_idx || !out_scores) return fail(ILRE_EINVAL, "out_idx or out_scores is null");
+    if ((rc = check_max_avg(L, sink, budget, max_kernels, n_max, avg_kernels, n_avg, false))) return rc;
+    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
+    const ilre::SelectJob job = max_avg_job(L, sink, budget, max_kernels, n_max, avg_kernels, n_avg);
+    const Layout lay = make_layout(p, L, (int64_t)Hq * Lq, job);
+    if ((rc = check_workspace(opts, lay.total))) return rc;
+    if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay))) return rc;
+    unsigned char *ws = (unsigned char *)opts->workspace;
+    const hipError_t e = ilre::launch_select(out_scores + sink, job, out_idx, out_count, ws + lay.select, lay.sel, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "selection launch");
     return ILRE_OK;
 }

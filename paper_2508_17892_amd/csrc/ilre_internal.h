@@ -60,26 +60,48 @@ hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_m
 
 // ---------------------------------------------------------------- selection (Algorithm 1)
 
-constexpr int kSelFine = 256;       // tokens a wavefront pools at a time ("fine chunk")
+constexpr int kSelFine = 256;       // elements a wavefront pools at a time ("fine chunk")
 constexpr int kSelBins = 2048;      // histogram bins per level: 11 key bits
 constexpr int kSelSmall = 2048;     // boundary lists up to this long join the candidates unrefined
-constexpr int kCandCap = 10240;     // candidate list capacity (>= ILRE_MAX_BUDGET + kSelSmall)
+constexpr int kCandCap = 10240;     // candidate capacity in tokens (>= ILRE_MAX_BUDGET + kSelSmall)
+
+// Two forms of Algorithm 1 share the selection kernels.  A "combination" j ranks the elements of a
+// source array (value descending, element ascending) and offers the tokens of its best elements:
+//   kSelWindowMax  stride-1 max pooling: source = the scores, element = token, value = maximum over a
+//                  window of radius r_j clipped to the context; candidates are never exhausted.
+//   kSelMaxAvg     the algorithm as printed: source = the cells of a strided max pooling (size = stride
+//                  = m), value = stride-1 average over n cells (zeros outside), element p stands for
+//                  tokens p*m .. p*m+m-1, and only the best K_m = B/m + 1 cells are candidates.
+enum SelMode { kSelWindowMax = 0, kSelMaxAvg = 1 };
+
+struct SelectJob {
+    int mode;                    // SelMode
+    int64_t L;                   // tokens the pooling sees (the context without its sink part)
+    int sink;                    // leading tokens that are always allocated (indices are offset by it)
+    int budget;
+    int n_max, n_avg;            // kSelWindowMax: n_max window sizes, n_avg = 1
+    const int32_t *max_kernels;  // host: window sizes w_j, or max-pooling sizes m_i
+    const int32_t *avg_kernels;  // host: average-pooling sizes n_j (kSelMaxAvg only)
+    int combos() const { return n_max * n_avg; }
+};
 
 struct SelectLayout {
     size_t hist;      // uint32 [2][n][kSelBins]  (level 1, level 2), then [2][kSelBins] of the pre-pass
     size_t ctrl;      // SelCtrl [n + 1]  (the last one belongs to the pre-pass)
-    size_t done;      // uint32 [2][n], then [2] of the pre-pass: workgroups finished per level and kernel
+    size_t done;      // uint32 [2][n], then [2] of the pre-pass: workgroups finished per level and combination
     size_t cmax;      // float [ceil(L / kSelFine)]: fine-chunk maxima (pruning pre-pass)
     size_t active;    // uint32 [ceil(L / kSelFine)]: fine chunks left after pruning
+    size_t cells;     // float: the max-pooled cell arrays, one per max kernel (kSelMaxAvg)
     size_t cand;      // uint64 [n][kCandCap]
-    size_t tie;       // uint64 [n][2][L]   (ping-pong lists of boundary elements)
+    size_t tie;       // uint64: per combination two ping-pong lists of boundary elements, each as long as its source
     size_t total;
 };
 
 struct SelCtrl {
-    uint32_t want;        // K_j: candidates needed = min(B_j + sum_{i<j} B_i, L)
+    uint32_t want;        // K_j: ranked elements that are candidates
     uint32_t share;       // B_j
-    uint32_t radius;      // (w_j - 1) / 2
+    uint32_t before;      // window: elements before and after the centre
+    uint32_t after;
     uint32_t bin1;        // level-1 bin (key bits 31..21) holding the K_j-th largest key
     uint32_t above1;      // keys in bins above it
     uint32_t need1;       // still needed from inside it
@@ -87,14 +109,21 @@ struct SelCtrl {
     uint32_t above2;      // keys of bin1 in level-2 bins above bin2
     uint32_t need2;       // still needed from inside (bin1, bin2)
     uint32_t cand_n;      // filled length of cand[j] after collect
-    uint32_t tie_n;       // filled length of tie[j][0]
-    uint32_t total_n;     // candidates after refine
-    uint32_t pad[4];
+    uint32_t tie_n;       // filled length of the first boundary list
+    uint32_t total_n;     // candidates (elements) after refine
+    uint32_t len;         // elements in the source array
+    uint32_t cell;        // tokens an element stands for (m; 1 in the window-max form)
+    uint32_t op;          // SelMode of the value function
+    uint64_t src_off;     // source array: floats from the base pointer the pooling kernels are given
+    uint64_t tie_off;     // boundary lists: uint64 words from the base of the tie region
+    uint32_t exact;       // 1: refine cuts the candidates to exactly `want`
+    uint32_t pad[3];
 };
 
-SelectLayout make_select_layout(int64_t L, int n_kernels);
+// Workspace carving for a job (only mode, L, counts and the max kernels are read).
+SelectLayout make_select_layout(const SelectJob &job);
 
-hipError_t launch_select(const float *scores, int64_t L, int budget, const int32_t *pool_kernels, int n_kernels,
-                         int32_t *out_idx, void *workspace, const SelectLayout &lay, hipStream_t s);
+hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
+                         void *workspace, const SelectLayout &lay, hipStream_t s);
 
 }  // namespace ilre

@@ -1,35 +1,45 @@
-// Context allocation (paper Section 3.2, Algorithm 1, stride-1 max-pool form) for gfx950.
+// Context allocation (paper Section 3.2, Algorithm 1) for gfx950, in two forms: one stride-1 max
+// pooling per kernel size (the "window-max" form), and the algorithm as printed (strided max pooling,
+// then stride-1 average pooling, one combination per pair of kernel sizes, the best K_m cells only).
 //
-// Algorithm 1 pools the scores per kernel size, takes a ranked candidate list per kernel and walks
-// it, skipping tokens an earlier kernel already allocated, until the kernel's share is filled.  The
-// share of kernel j can be met from its top K_j = B_j + (shares of the kernels before it) ranked
-// tokens, whatever the earlier kernels took, so the candidate sets are independent of each other and
-// are built for all kernel sizes at once:
+// Algorithm 1 pools the scores per combination, takes a ranked candidate list per combination and
+// walks it, skipping tokens an earlier combination already allocated, until the combination's share
+// is filled.  What a combination's candidates are does not depend on the combinations before it (in
+// the window-max form its share can be met from its top K_j = B_j + (shares before it) ranked tokens,
+// whatever the earlier ones took; in the printed form K_m is given), so the candidate sets are built
+// for all combinations at once:
 //
-//   sel_init     clears histograms and counters
-//   pool_hist<1> wavefronts share out the 256-token "fine chunks": scores + halo into the wavefront's
-//                own LDS buffers, sliding maximum by doubling (no block barriers), a 2048-bin LDS
-//                histogram of the top 11 bits of the pooled score's order-preserving key, added to the
-//                kernel's global histogram.  The last workgroup of a kernel size to finish locates
-//                the bin holding its K_j-th largest key.
+//   cell_max     printed form only: the strided max pooling, one cell array per max kernel
+//   sel_init     clears histograms and counters, writes each combination's control block
+//   pool_hist<1> wavefronts share out the 256-element "fine chunks" of the source array (the scores, or
+//                a cell array): elements + halo into the wavefront's own LDS buffers, pooled value
+//                (sliding maximum by doubling, or the average summed left to right), a 2048-bin LDS
+//                histogram of the top 11 bits of the value's order-preserving key, added to the
+//                combination's global histogram.  The last workgroup of a combination to finish
+//                locates the bin holding its K_j-th largest key.
 //   pool_hist<2> same pooling; histogram of the next 11 bits of the keys inside that bin; the last
 //                workgroup locates the 22-bit prefix of the K_j-th largest key.
-//   collect      keys above the prefix go to the kernel's candidate list, keys that share it to a
-//                boundary list (a few dozen on real scores; everything on all-equal scores)
-//   refine       per kernel: a boundary list longer than kSelSmall is radix-selected down (8 bits a
-//                pass, survivors compacted) to what is needed; the rest joins the candidates
-//   allocate     one workgroup walks the kernels in order: candidates not yet allocated (LDS hash
-//                set), exact radix select of the B_j largest among them in registers, then the
-//                allocated set sorted ascending.
+//   collect      keys above the prefix go to the combination's candidate list, keys that share it to
+//                a boundary list (a few dozen on real scores; everything on all-equal scores)
+//   refine       per combination: the boundary list is radix-selected down (8 bits a pass, survivors
+//                compacted) to what is needed -- in the window-max form only while it is longer than
+//                kSelSmall, extra candidates rank last and are harmless; in the printed form to
+//                exactly K_m elements -- and joins the candidates
+//   allocate     one workgroup walks the combinations in order: the tokens of the candidate elements
+//                that are not yet allocated (LDS hash set), exact radix select of the B_j largest
+//                among them in registers, then the allocated set sorted ascending behind the sink part.
 //
-// Long contexts (L >= 4M and >= 1024 tokens per budgeted token) start with a pruning pre-pass: the
-// maximum of every fine chunk (one streaming read of the scores), the 22-bit prefix of the budget-th
-// largest of those maxima (the same two histogram passes, run on the maxima), and the list of fine
-// chunks that can still hold an admitted token; the three pooling passes then visit only that list.
+// Long contexts in the window-max form (L >= 4M and >= 1024 tokens per budgeted token) start with a
+// pruning pre-pass: the maximum of every fine chunk (one streaming read of the scores), the 22-bit
+// prefix of the budget-th largest of those maxima (the same two histogram passes, run on the maxima),
+// and the list of fine chunks that can still hold an admitted token; the three pooling passes then
+// visit only that list.
 //
-// Ranking is (pooled score descending, token index ascending): the 64-bit key is the ordered score
-// bits above the complemented index, so all keys are distinct and every step is order-independent;
-// the integer atomics only reserve list slots and build histograms, and the result is deterministic.
+// Ranking is (pooled value descending, token index ascending): the 64-bit key is the ordered value
+// bits above the complemented element index, so all keys are distinct and every step is
+// order-independent; the integer atomics only reserve list slots and build histograms, and the result
+// is deterministic.  An element of m tokens ranks its tokens in ascending order, which is the order
+// the same key gives them once the element index is replaced by the token index.
 #include "ilre_internal.h"
 
 namespace ilre {
@@ -44,18 +54,26 @@ constexpr int kHashSlots = 16384;                 // >= 2 * ILRE_MAX_BUDGET
 constexpr int kKeysPerThread = kCandCap / kThreads;
 constexpr int kBuckets = 4096;                       // final counting sort (3 * kBuckets <= kHashSlots)
 
+// Per-combination description, host -> sel_init (by value), which copies it into the control blocks.
 struct SelParams {
     int n;
-    int64_t L;
-    uint32_t radius[ILRE_MAX_POOL_KERNELS];
-    uint32_t share[ILRE_MAX_POOL_KERNELS];
-    uint32_t want[ILRE_MAX_POOL_KERNELS];
+    uint32_t op, exact;
+    uint32_t before[ILRE_MAX_POOL_KERNELS], after[ILRE_MAX_POOL_KERNELS];
+    uint32_t share[ILRE_MAX_POOL_KERNELS], want[ILRE_MAX_POOL_KERNELS];
+    uint32_t len[ILRE_MAX_POOL_KERNELS], cell[ILRE_MAX_POOL_KERNELS];
+    uint64_t src_off[ILRE_MAX_POOL_KERNELS], tie_off[ILRE_MAX_POOL_KERNELS];
 };
 
-// Order-preserving map of a finite float onto uint32 (larger float -> larger key).
+struct CellParams {
+    int n;
+    uint32_t m[ILRE_MAX_POOL_KERNELS], len[ILRE_MAX_POOL_KERNELS];
+    uint64_t off[ILRE_MAX_POOL_KERNELS];
+};
+
+// Order-preserving map of a finite float onto uint32 (larger float -> larger key; the two zeros share one).
 __device__ __forceinline__ uint32_t ordered_bits(float x)
 {
-    const uint32_t b = __float_as_uint(x);
+    const uint32_t b = __float_as_uint(x + 0.0f);  // -0 ranks with +0
     return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
@@ -114,47 +132,99 @@ __global__ __launch_bounds__(kThreads) void sel_init(const SelParams prm, uint32
         SelCtrl c{};
         c.want = prm.want[j];
         c.share = prm.share[j];
-        c.radius = prm.radius[j];
+        c.before = prm.before[j];
+        c.after = prm.after[j];
         c.bin1 = kSelBins;
         c.bin2 = kSelBins;
+        c.len = prm.len[j];
+        c.cell = prm.cell[j];
+        c.op = prm.op;
+        c.src_off = prm.src_off[j];
+        c.tie_off = prm.tie_off[j];
+        c.exact = prm.exact;
         ctrl[j] = c;
-        done[j] = 0;          // [2][n]: workgroups finished per histogram level and kernel
+        done[j] = 0;          // [2][n]: workgroups finished per histogram level and combination
         done[prm.n + j] = 0;
     }
 }
 
-// The fine chunks (kSelFine tokens) a pooling pass visits: all of them, or a list built by the
-// pruning pre-pass.
+// MaxPooling of Algorithm 1 with size = stride = m: cell p = max(body[p*m .. p*m+m-1]) for the whole
+// cells; the tokens after the last whole cell belong to none.  grid = (workgroups, max kernels).
+__global__ __launch_bounds__(kPoolThreads) void cell_max(const float *body, const CellParams cp, float *cells)
+{
+    const int i = blockIdx.y;
+    const uint32_t m = cp.m[i], len = cp.len[i];
+    float *out = cells + cp.off[i];
+    for (uint32_t p = blockIdx.x * kPoolThreads + threadIdx.x; p < len; p += gridDim.x * kPoolThreads) {
+        const float *src = body + (size_t)p * m;
+        float v = src[0];
+        for (uint32_t u = 1; u < m; ++u) v = fmaxf(v, src[u]);
+        out[p] = v;
+    }
+}
+
+// The fine chunks (kSelFine elements) a pooling pass visits: all of the source array, or a list built
+// by the pruning pre-pass.
 struct Entries {
     const uint32_t *list;    // null: entry i is fine chunk i
     const uint32_t *list_n;  // device count of list entries
-    uint32_t nfine;          // ceil(L / kSelFine)
 };
-__device__ __forceinline__ uint32_t entry_count(const Entries &e) { return e.list ? load_u32(e.list_n) : e.nfine; }
+__device__ __forceinline__ uint32_t entry_count(const Entries &e, uint32_t len)
+{
+    return e.list ? load_u32(e.list_n) : (len + kSelFine - 1) / kSelFine;
+}
 __device__ __forceinline__ uint32_t entry_chunk(const Entries &e, uint32_t i) { return e.list ? e.list[i] : i; }
 
 // A wavefront's LDS operations complete in order; waiting for them (and telling the compiler that
 // memory changed) is all the synchronisation a wavefront-private buffer needs.
 __device__ __forceinline__ void lds_wave_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-// Pooled scores of this lane's kPerThread tokens of fine chunk `fc` for window radius r, computed by
-// one wavefront in its own LDS buffers b0/b1 (kSelFine + 2r floats each):
-// pooled[t] = max(score[u] : |u - t| <= r, 0 <= u < L)   (MaxPooling step of Algorithm 1 at stride 1,
-// window clipped to the context).  Sliding maximum by doubling: m_p[i] = max(score[i .. i+p-1]) for
-// p = 1, 2, 4, ... <= w, then two overlapping windows of length p cover the window of length w = 2r+1.
-__device__ __forceinline__ void pooled_wave(const float *scores, int64_t L, int64_t fc, int r, float *b0, float *b1,
-                                            float (&out)[kPerThread])
+// What a combination computes from its source array.
+struct Pooling {
+    const float *src;
+    int64_t len;        // elements in src
+    int before, after;  // window [e - before, e + after]
+    int op;             // SelMode
+};
+__device__ __forceinline__ Pooling pooling_of(const float *vals, const SelCtrl &c)
+{
+    return Pooling{vals + c.src_off, (int64_t)c.len, (int)c.before, (int)c.after, (int)c.op};
+}
+__device__ __forceinline__ size_t pool_lds_floats(int before, int after) { return (size_t)(kSelFine + before + after); }
+
+// Pooled values of this lane's kPerThread elements (lane + 64k) of fine chunk `fc`, computed by one
+// wavefront in its own LDS buffers b0/b1 (kSelFine + before + after floats each).
+//   kSelWindowMax: pooled[e] = max(src[u] : e - before <= u <= e + after, 0 <= u < len)  (MaxPooling at
+//     stride 1, window clipped to the context).  Sliding maximum by doubling: m_p[i] = max(src[i ..
+//     i+p-1]) for p = 1, 2, 4, ... <= w, then two overlapping windows of length p cover the window.
+//   kSelMaxAvg: pooled[e] = (src[e-before] + ... + src[e+after]) / w with zeros outside the array,
+//     summed left to right in fp32 and divided with round-to-nearest (AvgPooling at stride 1).
+__device__ __forceinline__ void pooled_wave(const Pooling &pl, int64_t fc, float *b0, float *b1, float (&out)[kPerThread])
 {
     const int lane = threadIdx.x & 63;
-    const int len = kSelFine + 2 * r;
-    const int64_t first = fc * kSelFine - r;
+    const int len = kSelFine + pl.before + pl.after;
+    const int64_t first = fc * kSelFine - pl.before;
+    const float pad = pl.op == kSelMaxAvg ? 0.0f : -INFINITY;
     lds_wave_sync();  // the previous chunk's reads of these buffers are done
     for (int i = lane; i < len; i += 64) {
-        const int64_t tok = first + i;
-        b0[i] = (tok >= 0 && tok < L) ? scores[tok] : -INFINITY;
+        const int64_t e = first + i;
+        b0[i] = (e >= 0 && e < pl.len) ? pl.src[e] : pad;
     }
     lds_wave_sync();
-    const int w = 2 * r + 1;
+    const int w = pl.before + pl.after + 1;
+    if (pl.op == kSelMaxAvg) {
+        float sum[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) sum[k] = 0.0f;
+        for (int u = 0; u < w; ++u) {
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) sum[k] = sum[k] + b0[lane + k * 64 + u];
+        }
+        const float div = (float)w;
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) out[k] = __fdiv_rn(sum[k], div);
+        return;
+    }
     int p = 1;
     float *src = b0, *dst = b1;
     while (2 * p <= w) {
@@ -228,34 +298,34 @@ __device__ __forceinline__ void wave_append(bool pred, T item, T *list, uint32_t
     if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = item;
 }
 
-// LEVEL 1: histogram of key bits 31..21 over the visited tokens.  LEVEL 2: of bits 20..10 over the
-// tokens whose bits 31..21 equal the kernel's level-1 bin.  grid = (workgroups, kernel sizes); the
-// wavefronts of the grid share out the entries.
+// LEVEL 1: histogram of key bits 31..21 over the visited elements.  LEVEL 2: of bits 20..10 over the
+// elements whose bits 31..21 equal the combination's level-1 bin.  grid = (workgroups, combinations);
+// the wavefronts of a grid row share out the entries.
 template <int LEVEL>
-__global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
-                                                          uint32_t *hist_all, uint32_t *done, const Entries ent)
+__global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int n, SelCtrl *ctrl, uint32_t *hist_all,
+                                                          uint32_t *done, const Entries ent)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t lh[kSelBins];
     __shared__ uint32_t is_last;
-    const int j = blockIdx.y, n = prm.n;
-    const int r = (int)prm.radius[j];
+    const int j = blockIdx.y;
+    const Pooling pl = pooling_of(vals, ctrl[j]);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t *hist = hist_all + (size_t)(LEVEL - 1) * n * kSelBins;
-    float *b0 = (float *)smem + (size_t)wave * 2 * (kSelFine + 2 * r);
-    float *b1 = b0 + kSelFine + 2 * r;
+    float *b0 = (float *)smem + (size_t)wave * 2 * pool_lds_floats(pl.before, pl.after);
+    float *b1 = b0 + pool_lds_floats(pl.before, pl.after);
     const uint32_t bin1 = LEVEL == 2 ? ctrl[j].bin1 : 0;
     for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
     __syncthreads();
-    const uint32_t nent = entry_count(ent);
+    const uint32_t nent = entry_count(ent, (uint32_t)pl.len);
     for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
         const int64_t fc = entry_chunk(ent, e);
         float pooled[kPerThread];
-        pooled_wave(scores, L, fc, r, b0, b1, pooled);
+        pooled_wave(pl, fc, b0, b1, pooled);
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
-            const int64_t tok = fc * kSelFine + lane + k * 64;
-            if (tok >= L) continue;
+            const int64_t el = fc * kSelFine + lane + k * 64;
+            if (el >= pl.len) continue;
             const uint32_t key = ordered_bits(pooled[k]);
             if (LEVEL == 1)
                 atomicAdd(&lh[key >> 21], 1u);
@@ -268,8 +338,8 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *scores, i
         const uint32_t c = lh[i];
         if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
     }
-    // The last workgroup of kernel j to get here sees its histogram complete and locates the bin.  Each thread
-    // waits until its histogram atomics have been performed, then one thread counts the workgroup in
+    // The last workgroup of combination j to get here sees its histogram complete and locates the bin.  Each
+    // thread waits until its histogram atomics have been performed, then one thread counts the workgroup in
     // (fences here cost tens of microseconds: an agent-scope release writes the L2 back).
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -280,31 +350,31 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *scores, i
     if (is_last) find_bins<LEVEL>(hist, ctrl, j);
 }
 
-__global__ __launch_bounds__(kPoolThreads) void collect(const float *scores, int64_t L, const SelParams prm, SelCtrl *ctrl,
-                                                        uint64_t *cand, uint64_t *tie, const Entries ent)
+__global__ __launch_bounds__(kPoolThreads) void collect(const float *vals, SelCtrl *ctrl, uint64_t *cand, uint64_t *tie,
+                                                        const Entries ent)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int j = blockIdx.y;
-    const int r = (int)prm.radius[j];
+    const Pooling pl = pooling_of(vals, ctrl[j]);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t bin1 = ctrl[j].bin1, bin2 = ctrl[j].bin2;
-    if (bin1 >= (uint32_t)kSelBins || bin2 >= (uint32_t)kSelBins) return;  // nothing wanted from this kernel
+    if (bin1 >= (uint32_t)kSelBins || bin2 >= (uint32_t)kSelBins) return;  // nothing wanted from this combination
     const uint32_t prefix = (bin1 << 11) | bin2;  // 22-bit prefix of the K_j-th largest key
-    float *b0 = (float *)smem + (size_t)wave * 2 * (kSelFine + 2 * r);
-    float *b1 = b0 + kSelFine + 2 * r;
+    float *b0 = (float *)smem + (size_t)wave * 2 * pool_lds_floats(pl.before, pl.after);
+    float *b1 = b0 + pool_lds_floats(pl.before, pl.after);
     uint64_t *cand_j = cand + (size_t)j * kCandCap;
-    uint64_t *tie_j = tie + (size_t)j * 2 * (size_t)L;
-    const uint32_t nent = entry_count(ent);
+    uint64_t *tie_j = tie + ctrl[j].tie_off;
+    const uint32_t nent = entry_count(ent, (uint32_t)pl.len);
     for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
         const int64_t fc = entry_chunk(ent, e);
         float pooled[kPerThread];
-        pooled_wave(scores, L, fc, r, b0, b1, pooled);
+        pooled_wave(pl, fc, b0, b1, pooled);
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
-            const int64_t tok = fc * kSelFine + lane + k * 64;
-            const bool valid = tok < L;
+            const int64_t el = fc * kSelFine + lane + k * 64;
+            const bool valid = el < pl.len;
             const uint32_t p22 = valid ? ordered_bits(pooled[k]) >> 10 : 0;
-            const uint64_t key = make_key(pooled[k], (uint32_t)tok);
+            const uint64_t key = make_key(pooled[k], (uint32_t)el);
             wave_append(valid && p22 > prefix, key, cand_j, &ctrl[j].cand_n);
             wave_append(valid && p22 == prefix, key, tie_j, &ctrl[j].tie_n);
         }
@@ -374,9 +444,10 @@ __global__ __launch_bounds__(kPoolThreads) void mark_active(const float *cm, uin
     wave_append(active, c, list, &pctrl->cand_n);
 }
 
-// Boundary list -> candidates.  Short lists (the normal case) are appended whole: candidates below
-// the cut are harmless, they rank last.  Long ones are radix-selected down first.
-__global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand, uint64_t *tie, int64_t L)
+// Boundary list -> candidates.  Window-max form: short lists (the normal case) are appended whole,
+// candidates below the cut are harmless, they rank last; long ones are radix-selected down first.
+// Printed form: the list is always cut to what the K_m-cell cap leaves.
+__global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand, uint64_t *tie)
 {
     __shared__ uint32_t h[256];
     __shared__ uint32_t cnt[2];
@@ -384,15 +455,16 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
 
     const int j = blockIdx.x;
     uint64_t *cand_j = cand + (size_t)j * kCandCap;
-    uint64_t *A = tie + (size_t)j * 2 * (size_t)L;
-    uint64_t *B = A + L;
+    uint64_t *A = tie + ctrl[j].tie_off;
+    uint64_t *B = A + ctrl[j].len;
     uint32_t nA = ctrl[j].tie_n;
     uint32_t need = ctrl[j].need2;
     uint32_t candn = ctrl[j].cand_n;
+    const uint32_t keep_small = ctrl[j].exact ? 0u : (uint32_t)kSelSmall;
     const int lane = threadIdx.x & 63;
 
     // The list shares its top 22 key bits (key64 bits 63..42).  Peel 8 more bits a pass.
-    for (int shift = 40; shift >= 0 && nA > (uint32_t)kSelSmall && need < nA; shift -= 8) {
+    for (int shift = 40; shift >= 0 && nA > keep_small && need < nA; shift -= 8) {
         if (threadIdx.x < 256) h[threadIdx.x] = 0;
         if (threadIdx.x < 2) cnt[threadIdx.x] = 0;
         __syncthreads();
@@ -451,10 +523,11 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
 
 __device__ __forceinline__ uint32_t hash_slot(uint32_t token) { return (token * 0x9E3779B1u) >> 18; }
 
-// Algorithm 1's walk: kernels in the order given; from kernel j's candidates the B_j largest keys
-// whose tokens are not yet allocated; finally the allocated set in ascending order.
-__global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out,
-                                                     int bucket_shift, int32_t *out_idx)
+// Algorithm 1's walk: combinations in the order given; from combination j's candidate tokens (the m
+// tokens of each candidate element) the B_j largest keys whose tokens are not yet allocated; finally
+// the sink indices followed by the allocated set in ascending order, the unused tail set to -1.
+__global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out, int sink,
+                                                     int bucket_shift, int32_t *out_idx, int32_t *out_count)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t *table = (uint32_t *)smem;  // kHashSlots
@@ -471,12 +544,23 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
 
     uint64_t key[kKeysPerThread];
     auto fetch = [&](int j, uint64_t(&dst)[kKeysPerThread]) {
-        const uint32_t cn = j < n ? ctrl[j].total_n : 0;
-        const uint64_t *cand_j = cand + (size_t)(j < n ? j : 0) * kCandCap;
+        const uint32_t m = ctrl[j].cell;
+        const uint32_t cn = ctrl[j].total_n * m;  // candidate tokens (<= kCandCap by the host's limits)
+        const uint64_t *cand_j = cand + (size_t)j * kCandCap;
 #pragma unroll
         for (int k = 0; k < kKeysPerThread; ++k) {
             const uint32_t i = threadIdx.x + k * kThreads;
-            dst[k] = i < cn ? cand_j[i] : 0;  // 0 is below every real key
+            uint64_t v = 0;  // 0 is below every real key
+            if (i < cn) {
+                if (m == 1) {
+                    v = cand_j[i];
+                } else {
+                    const uint32_t el = i / m;
+                    const uint64_t ek = cand_j[el];
+                    v = (ek & 0xFFFFFFFF00000000ull) | (uint64_t)(0xFFFFFFFFu - (key_token(ek) * m + (i - el * m)));
+                }
+            }
+            dst[k] = v;
         }
     };
     __syncthreads();
@@ -674,68 +758,135 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
         const uint32_t s0 = start[bkt], s1 = s0 + cnt[bkt];
         uint32_t rank = s0;
         for (uint32_t q = s0; q < s1; ++q) rank += grp[q] < t ? 1u : 0u;
-        out_idx[rank] = (int32_t)t;
+        out_idx[sink + rank] = (int32_t)(t + sink);
     }
-    for (int i = nsel + threadIdx.x; i < n_out; i += kThreads) out_idx[i] = -1;
+    for (int i = threadIdx.x; i < sink; i += kThreads) out_idx[i] = i;
+    for (int i = nsel + threadIdx.x; i < n_out; i += kThreads) out_idx[sink + i] = -1;
+    if (threadIdx.x == 0 && out_count) *out_count = sink + (int32_t)nsel;
 }
 
 }  // namespace
 
-SelectLayout make_select_layout(int64_t L, int n_kernels)
+// Elements of combination j's source array and the tokens one element stands for.
+static void combo_shape(const SelectJob &job, int j, int64_t &len, int &cell)
+{
+    if (job.mode == kSelMaxAvg) {
+        cell = job.max_kernels[j / job.n_avg];
+        len = job.L / cell;
+    } else {
+        cell = 1;
+        len = job.L;
+    }
+}
+
+SelectLayout make_select_layout(const SelectJob &job)
 {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     SelectLayout lay{};
-    const size_t nfine = (size_t)((L + kSelFine - 1) / kSelFine);
+    const int n = job.combos() > 0 ? job.combos() : 1;
+    const size_t nfine = (size_t)((job.L + kSelFine - 1) / kSelFine);
     size_t off = 0;
     lay.hist = off;
-    off = up(off + 2 * (size_t)(n_kernels + 1) * kSelBins * sizeof(uint32_t));  // + the pre-pass's own pair
+    off = up(off + 2 * (size_t)(n + 1) * kSelBins * sizeof(uint32_t));  // + the pre-pass's own pair
     lay.ctrl = off;
-    off = up(off + (size_t)(n_kernels + 1) * sizeof(SelCtrl));
+    off = up(off + (size_t)(n + 1) * sizeof(SelCtrl));
     lay.done = off;
-    off = up(off + 2 * (size_t)(n_kernels + 1) * sizeof(uint32_t));
+    off = up(off + 2 * (size_t)(n + 1) * sizeof(uint32_t));
     lay.cmax = off;
     off = up(off + nfine * sizeof(float));
     lay.active = off;
     off = up(off + nfine * sizeof(uint32_t));
+    lay.cells = off;
+    size_t ncell = 0, ntie = 0;
+    if (job.mode == kSelMaxAvg) {
+        for (int i = 0; i < job.n_max; ++i) ncell += (size_t)(job.L / job.max_kernels[i]);
+        ntie = 2 * ncell * (size_t)job.n_avg;
+    } else {
+        ntie = 2 * (size_t)job.L * (size_t)n;
+    }
+    off = up(off + ncell * sizeof(float));
     lay.cand = off;
-    off = up(off + (size_t)n_kernels * kCandCap * sizeof(uint64_t));
+    off = up(off + (size_t)n * kCandCap * sizeof(uint64_t));
     lay.tie = off;
-    off = up(off + (size_t)n_kernels * 2 * (size_t)L * sizeof(uint64_t));
+    off = up(off + ntie * sizeof(uint64_t));
     lay.total = off;
     return lay;
 }
 
-hipError_t launch_select(const float *scores, int64_t L, int budget, const int32_t *pool_kernels, int n_kernels,
-                         int32_t *out_idx, void *workspace, const SelectLayout &lay, hipStream_t s)
+hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
+                         void *workspace, const SelectLayout &lay, hipStream_t s)
 {
-    SelParams prm{};
-    prm.n = n_kernels;
-    prm.L = L;
-    const int base = budget / n_kernels, rem = budget % n_kernels;
-    int64_t before = 0;
-    int rmax = 0;
-    for (int j = 0; j < n_kernels; ++j) {
-        const int share = base + (j < rem ? 1 : 0);
-        const int64_t want = before + share < L ? before + share : L;
-        prm.radius[j] = (uint32_t)((pool_kernels[j] - 1) / 2);
-        prm.share[j] = (uint32_t)share;
-        prm.want[j] = (uint32_t)want;
-        before += share;
-        if ((int)prm.radius[j] > rmax) rmax = (int)prm.radius[j];
-    }
+    const int64_t L = job.L;
+    const int n = job.combos();
+    const int budget = job.budget;
+    const int n_out = (int)(budget < L ? budget : L);
     unsigned char *ws = (unsigned char *)workspace;
     uint32_t *hist = (uint32_t *)(ws + lay.hist);
     SelCtrl *ctrl = (SelCtrl *)(ws + lay.ctrl);
     uint32_t *done = (uint32_t *)(ws + lay.done);
     uint64_t *cand = (uint64_t *)(ws + lay.cand);
     uint64_t *tie = (uint64_t *)(ws + lay.tie);
-    const int n_out = (int)(budget < L ? budget : L);
-    const uint32_t nfine = (uint32_t)((L + kSelFine - 1) / kSelFine);
-    const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)(kSelFine + 2 * rmax) * sizeof(float);
+    float *cells = (float *)(ws + lay.cells);
     const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + 2 * (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
     int bucket_shift = 0;
     while (((int64_t)kBuckets << bucket_shift) < L) ++bucket_shift;
-    // Workgroups per kernel size in the pooling passes; beyond the cap the wavefronts loop over the
+
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void *)allocate, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
+    if (L == 0) {  // nothing but the sink part
+        hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, 0, 0, job.sink, 0, out_idx, out_count);
+        return hipGetLastError();
+    }
+
+    // B_c: floor(B / n), the first B mod n combinations one more.  K_j: window-max form, what the
+    // earlier shares could have taken plus the own share; printed form, K_m = B / m + 1 cells.
+    SelParams prm{};
+    CellParams cp{};
+    prm.n = n;
+    prm.op = (uint32_t)job.mode;
+    prm.exact = job.mode == kSelMaxAvg ? 1u : 0u;
+    const int base = budget / n, rem = budget % n;
+    int64_t before = 0, tie_off = 0, len_max = 0;
+    int halo_max = 0;
+    uint64_t cell_off = 0;
+    for (int j = 0; j < n; ++j) {
+        const int share = base + (j < rem ? 1 : 0);
+        int64_t len;
+        int cell;
+        combo_shape(job, j, len, cell);
+        prm.share[j] = (uint32_t)share;
+        prm.len[j] = (uint32_t)len;
+        prm.cell[j] = (uint32_t)cell;
+        prm.tie_off[j] = (uint64_t)tie_off;
+        tie_off += 2 * len;
+        if (job.mode == kSelMaxAvg) {
+            const int i = j / job.n_avg, na = job.avg_kernels[j % job.n_avg];
+            if (j % job.n_avg == 0) {
+                cp.m[i] = (uint32_t)cell;
+                cp.len[i] = (uint32_t)len;
+                cp.off[i] = cell_off;
+                cell_off += (uint64_t)len;
+            }
+            const int64_t km = (int64_t)budget / cell + 1;
+            prm.want[j] = (uint32_t)(km < len ? km : len);
+            prm.before[j] = (uint32_t)((na - 1) / 2);
+            prm.after[j] = (uint32_t)(na / 2);
+            prm.src_off[j] = cp.off[i];
+        } else {
+            const int64_t want = before + share < L ? before + share : L;
+            prm.want[j] = (uint32_t)want;
+            prm.before[j] = prm.after[j] = (uint32_t)((job.max_kernels[j] - 1) / 2);
+            prm.src_off[j] = 0;
+        }
+        before += share;
+        if ((int)(prm.before[j] + prm.after[j]) > halo_max) halo_max = (int)(prm.before[j] + prm.after[j]);
+        if (len > len_max) len_max = len;
+    }
+    cp.n = job.n_max;
+    const float *vals = job.mode == kSelMaxAvg ? cells : scores;
+    const uint32_t nfine = (uint32_t)((len_max + kSelFine - 1) / kSelFine);
+    const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)(kSelFine + halo_max) * sizeof(float);
+    // Workgroups per combination in the pooling passes; beyond the cap the wavefronts loop over the
     // entries.  The histogram passes end with one atomic per hot bin and workgroup on a handful of
     // addresses (about 13 ns each, serialised), so they use fewer, longer-running workgroups.
     auto pool_blocks = [](uint32_t entries, uint32_t cap) {
@@ -744,46 +895,50 @@ hipError_t launch_select(const float *scores, int64_t L, int budget, const int32
     };
     constexpr uint32_t kHistCap = 256, kCollectCap = 1024;
 
-    hipError_t e;
     if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)pool_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)allocate, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
 
-    Entries ent{nullptr, nullptr, nfine};
-    // Long contexts: visit only the fine chunks that can hold an admitted token.
-    if ((int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384) {
+    Entries ent{nullptr, nullptr};
+    uint32_t entries = nfine;
+    if (job.mode == kSelMaxAvg) {
+        uint32_t cb = (uint32_t)((len_max + kPoolThreads - 1) / kPoolThreads);
+        if (cb > 2048u) cb = 2048u;
+        if (cb) hipLaunchKernelGGL(cell_max, dim3(cb, job.n_max), dim3(kPoolThreads), 0, s, scores, cp, cells);
+    } else if ((int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384) {
+        // Long contexts: visit only the fine chunks that can hold an admitted token.
         float *cm = (float *)(ws + lay.cmax);
         uint32_t *active = (uint32_t *)(ws + lay.active);
-        uint32_t *phist = hist + 2 * (size_t)n_kernels * kSelBins;
-        SelCtrl *pctrl = ctrl + n_kernels;
-        uint32_t *pdone = done + 2 * (size_t)n_kernels;
+        uint32_t *phist = hist + 2 * (size_t)n * kSelBins;
+        SelCtrl *pctrl = ctrl + n;
+        uint32_t *pdone = done + 2 * (size_t)n;
         SelParams pp{};
         pp.n = 1;
-        pp.L = nfine;
+        pp.len[0] = nfine;
+        pp.cell[0] = 1;
         pp.want[0] = (uint32_t)n_out;
         const uint32_t nfine2 = (nfine + kSelFine - 1) / kSelFine;
-        const Entries all{nullptr, nullptr, nfine2};
+        const Entries all{nullptr, nullptr};
         const size_t lds0 = (size_t)kPoolWaves * 2 * kSelFine * sizeof(float);
         hipLaunchKernelGGL(chunk_max, dim3(2048), dim3(kPoolThreads), 0, s, scores, L, nfine, cm);
         hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, pp, phist, pctrl, pdone);
-        hipLaunchKernelGGL(pool_hist<1>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, (int64_t)nfine, pp, pctrl, phist, pdone, all);
-        hipLaunchKernelGGL(pool_hist<2>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, (int64_t)nfine, pp, pctrl, phist, pdone, all);
-        const int reach = (rmax + kSelFine - 1) / kSelFine;
+        hipLaunchKernelGGL(pool_hist<1>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, 1, pctrl, phist, pdone, all);
+        hipLaunchKernelGGL(pool_hist<2>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, 1, pctrl, phist, pdone, all);
+        const int reach = (halo_max / 2 + kSelFine - 1) / kSelFine;
         hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, cm, nfine, reach, pctrl, active);
-        ent = Entries{active, &pctrl->cand_n, nfine};
+        ent = Entries{active, &pctrl->cand_n};
+        // with a list the entry count is only known on the device: size the grid for the worst case the
+        // pruning rule is meant for (a few times the budget) and let the wavefronts loop
+        entries = 4u * (uint32_t)n_out + 1024u;
     }
-    // with a list the entry count is only known on the device: size the grid for the worst case the
-    // pruning rule is meant for (a few times the budget) and let the wavefronts loop
-    const uint32_t entries = ent.list ? 4u * (uint32_t)n_out + 1024u : nfine;
     const uint32_t hblocks = pool_blocks(entries, kHistCap), cblocks = pool_blocks(entries, kCollectCap);
 
-    hipLaunchKernelGGL(sel_init, dim3(n_kernels), dim3(kThreads), 0, s, prm, hist, ctrl, done);
-    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done, ent);
-    hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, hist, done, ent);
-    hipLaunchKernelGGL(collect, dim3(cblocks, n_kernels), dim3(kPoolThreads), pool_lds, s, scores, L, prm, ctrl, cand, tie, ent);
-    hipLaunchKernelGGL(refine, dim3(n_kernels), dim3(kThreads), 0, s, ctrl, cand, tie, L);
-    hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n_kernels, n_out, bucket_shift, out_idx);
+    hipLaunchKernelGGL(sel_init, dim3(n), dim3(kThreads), 0, s, prm, hist, ctrl, done);
+    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, vals, n, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, vals, n, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(collect, dim3(cblocks, n), dim3(kPoolThreads), pool_lds, s, vals, ctrl, cand, tie, ent);
+    hipLaunchKernelGGL(refine, dim3(n), dim3(kThreads), 0, s, ctrl, cand, tie);
+    hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n, n_out, job.sink, bucket_shift, out_idx, out_count);
     return hipGetLastError();
 }
 

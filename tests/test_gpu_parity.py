@@ -127,6 +127,68 @@ def test_select_exact_on_given_scores(name, L, kernels, budget, kind):
     assert got.tolist() == want.tolist()
 
 
+PAPER_MAX, PAPER_AVG = (2, 4, 8), tuple(range(1, 17))     # the paper's default pooling set (Section 3.2)
+
+MAX_AVG_CASES = [
+    # name, L, sink, max kernels, avg kernels, budget, kind of scores
+    ("paper_default_needles", 100000, 4, PAPER_MAX, PAPER_AVG, 4096, "needles"),
+    ("paper_default_ragged", 50001, 4, PAPER_MAX, PAPER_AVG, 1024, "random"),
+    ("snapkv_special_case", 30000, 0, (1,), (7,), 1000, "random"),
+    ("plain_topk", 20000, 0, (1,), (1,), 512, "random"),
+    ("one_max_avg", 40000, 4, (4,), (5,), 2048, "needles"),
+    ("odd_max_kernels", 33333, 3, (3, 5, 6, 7), (1, 2, 3, 4, 9), 3000, "random"),
+    ("candidates_exhausted", 3000, 2, (8, 8, 4), (1, 2, 3), 2500, "random"),
+    ("budget_exceeds_L", 700, 4, (2, 4), (1, 3), 5000, "random"),
+    ("budget_below_combination_count", 5000, 4, PAPER_MAX, PAPER_AVG, 5, "random"),
+    ("all_equal", 60000, 4, PAPER_MAX, (1, 2, 5, 16), 4096, "equal"),
+    ("plateaus", 70000, 0, (2, 8), (1, 4, 16), 4096, "few_values"),
+    ("two_values_heavy_ties", 150000, 4, (2, 4), (1, 2), 6000, "two_values"),
+    ("dense_background", 200000, 4, PAPER_MAX, PAPER_AVG, 4096, "narrow"),
+    ("signed_with_zeros", 25000, 1, (2, 3), (1, 2, 6), 800, "signed"),
+    ("wide_kernels", 90000, 0, (1024, 256), (1024, 33), 8192, "needles"),
+    ("L_below_max_kernel", 5, 0, (8, 2), (1, 3), 4, "random"),
+    ("sink_is_everything", 37, 37, (2,), (3,), 16, "random"),
+    ("sink_leaves_one_token", 38, 37, (1, 2), (3,), 16, "random"),
+    ("max_budget", 50000, 4, PAPER_MAX, PAPER_AVG, 8192, "random"),
+    ("one_million_paper_default", 1 << 20, 4, PAPER_MAX, PAPER_AVG, 4096, "needles"),
+]
+
+
+@pytest.mark.parametrize("name,L,sink,mk,ak,budget,kind", MAX_AVG_CASES, ids=[c[0] for c in MAX_AVG_CASES])
+def test_select_max_avg_exact_on_given_scores(name, L, sink, mk, ak, budget, kind):
+    """Algorithm 1 as printed (strided max pooling, average pooling, K_m cap, sink part): bit-exact with
+    the oracle on the same float32 scores, the unused tail of the output marked -1."""
+    _announce(f"select_max_avg {name} L={L} sink={sink} max={mk} avg={ak} budget={budget}")
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    if kind == "signed":
+        s = rng.standard_normal(L).astype(np.float32)
+        s[rng.random(L) < 0.3] = 0.0
+        s[rng.random(L) < 0.1] = -0.0
+    else:
+        s = _scores_for(kind, L, rng) if L > 300 else rng.random(L).astype(np.float32)
+    want = oracle.allocate_max_avg(s, mk, ak, budget, sink=sink)
+    got, count = il.ilre_select_max_avg(torch.from_numpy(s).cuda(), budget, mk, ak, sink)
+    torch.cuda.synchronize()
+    got, count = got.cpu().numpy(), int(count.item())
+    assert got.shape == (sink + min(budget, L - sink),) and got.dtype == np.int32
+    assert count == len(want)
+    assert got[:count].tolist() == want.tolist()
+    assert (got[count:] == -1).all()
+
+
+def test_select_max_avg_reuses_a_workspace():
+    """Two calls in a row on one workspace, the second smaller: nothing of the first leaks into it."""
+    _announce("select_max_avg workspace reuse")
+    rng = np.random.default_rng(11)
+    big, small = _scores_for("needles", 80000, rng), rng.random(9000).astype(np.float32)
+    ws = il.alloc_workspace_max_avg(80000, 1, 1, 1, 128, 4, PAPER_MAX, len(PAPER_AVG), il.ILRE_F32)
+    for s, budget in ((big, 4096), (small, 700), (big, 4096)):
+        want = oracle.allocate_max_avg(s, PAPER_MAX, PAPER_AVG, budget, sink=4)
+        got, count = il.ilre_select_max_avg(torch.from_numpy(s).cuda(), budget, PAPER_MAX, PAPER_AVG, 4, workspace=ws)
+        torch.cuda.synchronize()
+        assert got.cpu().numpy()[:int(count.item())].tolist() == want.tolist()
+
+
 def _end_to_end(inp, kernels, budget):
     wl = inp.workload
     q, k = to_device(inp.q), to_device(inp.k)
