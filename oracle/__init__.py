@@ -8,7 +8,7 @@ from __future__ import annotations
 import numpy as np
 
 from .allocation import (allocate, allocate_max_avg, avg_pool_same, max_pool_same, max_pool_strided, split_budget,
-                         thresholds)
+                         thresholds, thresholds_max_avg)
 from .scoring import MODE_MAX, MODE_SUM, num_threads, row_stats, scores
 
 
@@ -20,5 +20,13 @@ def recall(q, k, pool_kernels, budget, scale=None, mode=MODE_SUM):
     return idx, score
 
 
-__all__ = ["allocate", "allocate_max_avg", "avg_pool_same", "max_pool_strided", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
+def recall_max_avg(q, k, max_kernels, avg_kernels, budget, sink=0, scale=None, mode=MODE_SUM):
+    """Whole path with Algorithm 1 as printed: Eq. 4 over all positions (the sink part included), Eq. 5,
+    then the allocation decided on the fp32-rounded scores.  Returns (indices int64 ascending, score fp64[L])."""
+    score, _, _ = scores(q, k, scale=scale, mode=mode)
+    idx = allocate_max_avg(score.astype(np.float32), max_kernels, avg_kernels, budget, sink=sink)
+    return idx, score
+
+
+__all__ = ["recall_max_avg", "thresholds_max_avg", "allocate", "allocate_max_avg", "avg_pool_same", "max_pool_strided", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
            "num_threads", "recall", "MODE_SUM", "MODE_MAX"]

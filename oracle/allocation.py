@@ -160,3 +160,44 @@ def allocate_max_avg(score: np.ndarray, max_kernels: Sequence[int], avg_kernels:
                         added += 1
             combo += 1
     return np.concatenate([np.arange(sink), sink + np.flatnonzero(allocated)]).astype(np.int64)
+
+
+def thresholds_max_avg(score: np.ndarray, max_kernels: Sequence[int], avg_kernels: Sequence[int], budget: int,
+                       sink: int = 0):
+    """For the index-set comparison rule: replay allocate_max_avg and report, per combination, the pooled
+    value of every token (its cell's average; NaN for the sink part and for tokens after the last whole
+    cell), the value of the last cell that gave the combination a token (None if it took nothing) and the
+    value of the K_m-th ranked cell (None if every cell is a candidate)."""
+    L = score.shape[0]
+    body = score[sink:]
+    Lb = body.shape[0]
+    shares = split_budget(budget, len(max_kernels) * len(avg_kernels))
+    allocated = np.zeros(Lb, dtype=bool)
+    out = []
+    combo = 0
+    for m in max_kernels:
+        m = int(m)
+        cells = max_pool_strided(body, m)
+        k_m = budget // m + 1
+        cell_id = np.arange(cells.shape[0])
+        for n in avg_kernels:
+            pooled = avg_pool_same(cells, int(n))
+            ranked = np.lexsort((cell_id, -pooled.astype(np.float64)))
+            order = ranked[:k_m]
+            per_token = np.full(L, np.nan)
+            per_token[sink:sink + cells.shape[0] * m] = np.repeat(pooled.astype(np.float64), m)
+            added, last = 0, None
+            for p in order:
+                if added >= shares[combo]:
+                    break
+                for t in range(p * m, p * m + m):
+                    if added >= shares[combo]:
+                        break
+                    if not allocated[t]:
+                        allocated[t] = True
+                        added += 1
+                        last = float(pooled[p])
+            cap = float(pooled[ranked[k_m - 1]]) if k_m < cells.shape[0] else None
+            out.append((per_token, last, cap))
+            combo += 1
+    return out

@@ -89,8 +89,9 @@ __device__ __forceinline__ uint32_t load_u32(const uint32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Inclusive prefix sum over the 1024 threads of the block; wsum is 16 words of LDS scratch.
-// Every thread also receives the block total.  Contains two barriers.
+// Inclusive prefix sum over the THREADS threads of the block; wsum is THREADS / 64 words of LDS
+// scratch.  Every thread also receives the block total.  Contains two barriers.
+template <int THREADS>
 __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t x, uint32_t *wsum, uint32_t &total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -104,7 +105,7 @@ __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t x, uint32_t *w
     __syncthreads();
     uint32_t before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
         const uint32_t s = wsum[w];
         if (w < wave) before += s;
         all += s;
@@ -206,9 +207,27 @@ __device__ __forceinline__ void pooled_wave(const Pooling &pl, int64_t fc, float
     const int64_t first = fc * kSelFine - pl.before;
     const float pad = pl.op == kSelMaxAvg ? 0.0f : -INFINITY;
     lds_wave_sync();  // the previous chunk's reads of these buffers are done
-    for (int i = lane; i < len; i += 64) {
-        const int64_t e = first + i;
-        b0[i] = (e >= 0 && e < pl.len) ? pl.src[e] : pad;
+    // Loads are unconditional from a clamped address (padding is selected afterwards), so that a
+    // lane's loads are all in flight together instead of one memory latency after the other.
+    const int64_t last = pl.len - 1;
+    auto clamped = [&](int64_t e) { return pl.src[e < 0 ? 0 : (e > last ? last : e)]; };
+    {
+        float v[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) v[k] = clamped(first + lane + k * 64);
+        const int ih = kSelFine + lane;  // halo part: before + after <= 2 * 1023 elements
+        const float vh = clamped(first + ih);
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int64_t e = first + lane + k * 64;
+            b0[lane + k * 64] = (e >= 0 && e <= last) ? v[k] : pad;
+        }
+        if (ih < len) b0[ih] = (first + ih >= 0 && first + ih <= last) ? vh : pad;
+        for (int i = ih + 64; i < len; i += 64) {
+            const int64_t e = first + i;
+            const float x = clamped(e);
+            b0[i] = (e >= 0 && e <= last) ? x : pad;
+        }
     }
     lds_wave_sync();
     const int w = pl.before + pl.after + 1;
@@ -242,43 +261,51 @@ __device__ __forceinline__ void pooled_wave(const Pooling &pl, int64_t fc, float
     }
 }
 
-// For kernel j: the bin b with  count(bins > b) < need <= count(bins >= b), by one wavefront (lane l
-// scans 32 bins, descending).  LEVEL 1 reads `want`, LEVEL 2 the remainder left by level 1.
+// For combination j: the bin b with  count(bins > b) < need <= count(bins >= b), by one wavefront.
+// Lane l sums 32 bins (descending order of bins); a scan over the lanes finds the lane whose segment
+// holds the crossing, and a second scan over that segment's 32 bins (one bin a lane) finds the bin.
+// LEVEL 1 reads `want`, LEVEL 2 the remainder left by level 1.
 template <int LEVEL>
 __device__ void find_bins(const uint32_t *hist, SelCtrl *ctrl, int j)
 {
     const int lane = threadIdx.x & 63;
     constexpr int BPL = kSelBins / 64;
+    static_assert(BPL == 32, "the second scan maps one bin of a segment to each of 32 lanes");
     if (threadIdx.x < 64) {
         const uint32_t need = LEVEL == 1 ? ctrl[j].want : ctrl[j].need1;
         if (need == 0 || (LEVEL == 2 && ctrl[j].bin1 >= (uint32_t)kSelBins)) return;  // uniform in the wave
+        const uint32_t *hj = hist + (size_t)j * kSelBins;
         uint32_t sum = 0;
-#pragma unroll 8
-        for (int k = 0; k < BPL; ++k) sum += load_u32(&hist[(size_t)j * kSelBins + (kSelBins - 1 - (lane * BPL + k))]);
+#pragma unroll 16
+        for (int k = 0; k < BPL; ++k) sum += load_u32(&hj[kSelBins - 1 - (lane * BPL + k)]);
         uint32_t incl = sum;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const uint32_t y = __shfl_up(incl, d);
             if (lane >= d) incl += y;
         }
-        uint32_t above = incl - sum;
-        if (above < need && need <= incl) {  // one lane per kernel walks its 32 bins again
-#pragma unroll 1
-            for (int k = 0; k < BPL; ++k) {
-                const uint32_t bin = kSelBins - 1 - (lane * BPL + k);
-                const uint32_t own = load_u32(&hist[(size_t)j * kSelBins + bin]);
-                if (above < need && need <= above + own) {
-                    if (LEVEL == 1) {
-                        ctrl[j].bin1 = bin;
-                        ctrl[j].above1 = above;
-                        ctrl[j].need1 = need - above;
-                    } else {
-                        ctrl[j].bin2 = bin;
-                        ctrl[j].above2 = above;
-                        ctrl[j].need2 = need - above;
-                    }
-                }
-                above += own;
+        const uint64_t hit = __ballot(incl - sum < need && need <= incl);
+        if (hit == 0) return;  // fewer than `need` keys in all (never: need <= number of elements)
+        const int seg = __ffsll((unsigned long long)hit) - 1;
+        const uint32_t seg_above = __shfl(incl - sum, seg);
+        const uint32_t bin = kSelBins - 1 - (seg * BPL + (lane & 31));
+        const uint32_t own = lane < 32 ? load_u32(&hj[bin]) : 0u;
+        uint32_t in2 = own;
+#pragma unroll
+        for (int d = 1; d < 32; d <<= 1) {
+            const uint32_t y = __shfl_up(in2, d);
+            if (lane >= d) in2 += y;
+        }
+        const uint32_t above = seg_above + in2 - own;
+        if (lane < 32 && above < need && need <= above + own) {  // exactly one lane
+            if (LEVEL == 1) {
+                ctrl[j].bin1 = bin;
+                ctrl[j].above1 = above;
+                ctrl[j].need1 = need - above;
+            } else {
+                ctrl[j].bin2 = bin;
+                ctrl[j].above2 = above;
+                ctrl[j].need2 = need - above;
             }
         }
     }
@@ -447,7 +474,7 @@ __global__ __launch_bounds__(kPoolThreads) void mark_active(const float *cm, uin
 // Boundary list -> candidates.  Window-max form: short lists (the normal case) are appended whole,
 // candidates below the cut are harmless, they rank last; long ones are radix-selected down first.
 // Printed form: the list is always cut to what the K_m-cell cap leaves.
-__global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand, uint64_t *tie)
+__global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand, uint64_t *tie, uint32_t sort_n)
 {
     __shared__ uint32_t h[256];
     __shared__ uint32_t cnt[2];
@@ -518,14 +545,121 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
         B = t;
     }
     for (uint32_t i = threadIdx.x; i < nA; i += kThreads) cand_j[candn + i] = A[i];
-    if (threadIdx.x == 0) ctrl[j].total_n = candn + nA;
+    const uint32_t total = candn + nA;
+    if (threadIdx.x == 0) ctrl[j].total_n = total;
+    if (!ctrl[j].exact) return;  // uniform
+
+    // Printed form: hand the candidates to the allocation walk in rank order.  Bitonic sort of the
+    // keys (descending; padding keys of 0 sink to the end) in LDS, one barrier per stage.
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint64_t *srt = (uint64_t *)smem;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this workgroup's stores to cand_j have reached the L2
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < sort_n; i += kThreads)
+        srt[i] = i < total ? __hip_atomic_load(&cand_j[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+    __syncthreads();
+    for (uint32_t k = 2; k <= sort_n; k <<= 1) {
+        for (uint32_t d = k >> 1; d > 0; d >>= 1) {
+            for (uint32_t i = threadIdx.x; i < sort_n / 2; i += kThreads) {
+                const uint32_t lo = ((i & ~(d - 1)) << 1) | (i & (d - 1)), hi = lo + d;
+                const uint64_t a = srt[lo], b = srt[hi];
+                const bool descending = (lo & k) == 0;
+                if ((a < b) == descending) {
+                    srt[lo] = b;
+                    srt[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // The allocation walk wants tokens: element e stands for tokens e*m .. e*m+m-1, in that order.  The
+    // token list (uint32, total * m <= kCandCap entries) takes over the storage of the key list.
+    uint32_t *tokens = (uint32_t *)cand_j;
+    const uint32_t m = ctrl[j].cell;
+    for (uint32_t r = threadIdx.x; r < total * m; r += kThreads) {
+        const uint32_t el = r / m;
+        tokens[r] = key_token(srt[el]) * m + (r - el * m);
+    }
 }
 
 __device__ __forceinline__ uint32_t hash_slot(uint32_t token) { return (token * 0x9E3779B1u) >> 18; }
 
-// Algorithm 1's walk: combinations in the order given; from combination j's candidate tokens (the m
-// tokens of each candidate element) the B_j largest keys whose tokens are not yet allocated; finally
-// the sink indices followed by the allocated set in ascending order, the unused tail set to -1.
+// The allocated set I of Algorithm 1 as an open-addressing hash set of token indices in LDS.
+__device__ __forceinline__ bool is_allocated(const uint32_t *table, uint32_t token)
+{
+    uint32_t s = hash_slot(token);
+    while (true) {
+        const uint32_t t = table[s];
+        if (t == kEmpty) return false;
+        if (t == token) return true;
+        s = (s + 1) & (kHashSlots - 1);
+    }
+}
+__device__ __forceinline__ void mark_allocated(uint32_t *table, uint32_t token)
+{
+    uint32_t s = hash_slot(token);
+    while (true) {
+        const uint32_t old = atomicCAS(&table[s], kEmpty, token);
+        if (old == kEmpty || old == token) break;
+        s = (s + 1) & (kHashSlots - 1);
+    }
+}
+
+// Last step of both allocation kernels: the sink indices, then the nsel allocated tokens in ascending
+// order (counting sort on the high bits into kBuckets buckets, then each token's rank inside its bucket
+// by counting the smaller ones: deterministic whatever order the tokens arrived in), then -1 up to
+// sink + n_out.  table (the hash set, no longer needed) and the second half of sel are scratch.
+template <int THREADS>
+__device__ __forceinline__ void emit_ascending(uint32_t *table, uint32_t *sel, uint32_t *wsum, uint32_t nsel, int n_out,
+                                               int sink, int bucket_shift, int32_t *out_idx, int32_t *out_count)
+{
+    uint32_t *cnt = table;                  // the hash set is no longer needed
+    uint32_t *start = table + kBuckets;
+    uint32_t *fill = table + 2 * kBuckets;
+    uint32_t *grp = sel + ILRE_MAX_BUDGET;
+    for (int i = threadIdx.x; i < kBuckets; i += THREADS) {
+        cnt[i] = 0;
+        fill[i] = 0;
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nsel; i += THREADS) atomicAdd(&cnt[sel[i] >> bucket_shift], 1u);
+    __syncthreads();
+    {
+        constexpr int BPT = kBuckets / THREADS;
+        uint32_t own[BPT], sum = 0;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            own[k] = cnt[threadIdx.x * BPT + k];
+            sum += own[k];
+        }
+        uint32_t total;
+        uint32_t run = block_scan_inclusive<THREADS>(sum, wsum, total) - sum;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            start[threadIdx.x * BPT + k] = run;
+            run += own[k];
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nsel; i += THREADS) {
+        const uint32_t t = sel[i], bkt = t >> bucket_shift;
+        grp[start[bkt] + atomicAdd(&fill[bkt], 1u)] = t;
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nsel; i += THREADS) {
+        const uint32_t t = grp[i], bkt = t >> bucket_shift;
+        const uint32_t s0 = start[bkt], s1 = s0 + cnt[bkt];
+        uint32_t rank = s0;
+        for (uint32_t q = s0; q < s1; ++q) rank += grp[q] < t ? 1u : 0u;
+        out_idx[sink + rank] = (int32_t)(t + sink);
+    }
+    for (int i = threadIdx.x; i < sink; i += THREADS) out_idx[i] = i;
+    for (int i = nsel + threadIdx.x; i < n_out; i += THREADS) out_idx[sink + i] = -1;
+    if (threadIdx.x == 0 && out_count) *out_count = sink + (int32_t)nsel;
+}
+
+// Algorithm 1's walk, window-max form: kernels in the order given; from kernel j's candidates the B_j
+// largest keys whose tokens are not yet allocated; then the output.
 __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out, int sink,
                                                      int bucket_shift, int32_t *out_idx, int32_t *out_count)
 {
@@ -544,24 +678,16 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
 
     uint64_t key[kKeysPerThread];
     auto fetch = [&](int j, uint64_t(&dst)[kKeysPerThread]) {
-        const uint32_t m = ctrl[j].cell;
-        const uint32_t cn = ctrl[j].total_n * m;  // candidate tokens (<= kCandCap by the host's limits)
+        const uint32_t cn = ctrl[j].total_n;
         const uint64_t *cand_j = cand + (size_t)j * kCandCap;
 #pragma unroll
         for (int k = 0; k < kKeysPerThread; ++k) {
-            const uint32_t i = threadIdx.x + k * kThreads;
-            uint64_t v = 0;  // 0 is below every real key
-            if (i < cn) {
-                if (m == 1) {
-                    v = cand_j[i];
-                } else {
-                    const uint32_t el = i / m;
-                    const uint64_t ek = cand_j[el];
-                    v = (ek & 0xFFFFFFFF00000000ull) | (uint64_t)(0xFFFFFFFFu - (key_token(ek) * m + (i - el * m)));
-                }
-            }
-            dst[k] = v;
+            const uint32_t i = threadIdx.x + k * kThreads;  // < kCandCap: always inside the list's storage
+            dst[k] = cand_j[i];
         }
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k)
+            if (threadIdx.x + k * kThreads >= cn) dst[k] = 0;  // 0 is below every real key
     };
     __syncthreads();
 
@@ -579,19 +705,7 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
 #pragma unroll
         for (int k = 0; k < kKeysPerThread; ++k) {
             if (key[k] == 0) continue;
-            const uint32_t token = key_token(key[k]);
-            uint32_t s = hash_slot(token);
-            bool taken = false;
-            while (true) {
-                const uint32_t t = table[s];
-                if (t == kEmpty) break;
-                if (t == token) {
-                    taken = true;
-                    break;
-                }
-                s = (s + 1) & (kHashSlots - 1);
-            }
-            if (!taken) {
+            if (!is_allocated(table, key_token(key[k]))) {
                 free_mask |= 1u << k;
                 ++nfree;
                 vand &= key[k];
@@ -704,65 +818,166 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
             if ((take_mask >> k) & 1u) {
                 const uint32_t token = key_token(key[k]);
                 sel[pos++] = token;
-                uint32_t s = hash_slot(token);
-                while (true) {
-                    const uint32_t old = atomicCAS(&table[s], kEmpty, token);
-                    if (old == kEmpty || old == token) break;
-                    s = (s + 1) & (kHashSlots - 1);
-                }
+                mark_allocated(table, token);
             }
         }
         __syncthreads();
         nsel = nsel_ctr;
     }
     __syncthreads();
+    emit_ascending<kThreads>(table, sel, wsum, nsel, n_out, sink, bucket_shift, out_idx, out_count);
+}
 
-    // Ascending order of the nsel allocated tokens: counting sort on the high bits (kBuckets buckets),
-    // then each token's rank inside its bucket by counting the smaller ones.  Deterministic whatever
-    // order the tokens arrived in.
-    uint32_t *cnt = table;                  // the hash set is no longer needed
-    uint32_t *start = table + kBuckets;
-    uint32_t *fill = table + 2 * kBuckets;
-    uint32_t *grp = sel + ILRE_MAX_BUDGET;
-    for (int i = threadIdx.x; i < kBuckets; i += kThreads) {
-        cnt[i] = 0;
-        fill[i] = 0;
+// LDS writes of this wavefront done, then the workgroup barrier; global loads in flight stay in flight.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Algorithm 1's walk, printed form.  refine left combination j's candidate tokens in rank order (a
+// uint32 list in the storage of cand[j]).  Wavefront w owns the ranks [w*64*per,
+// (w+1)*64*per), lane l the ranks w*64*per + 64*i + l.  Each wavefront counts its free tokens with
+// ballots, one exchange through LDS gives every wavefront the number of free tokens ranked ahead of
+// it, and the first B_j free tokens are taken.  The next combination's tokens are fetched meanwhile.
+constexpr int kRankThreads = 1024;
+constexpr int kRankWaves = kRankThreads / 64;
+constexpr int kRankG = 5;                                                           // tokens of a lane are handled in groups
+constexpr int kRankGroups = (kCandCap / kRankThreads + kRankG - 1) / kRankG;
+constexpr int kRankPer = kRankGroups * kRankG;                                      // tokens per lane at most
+static_assert(kRankPer <= 64, "free tokens of a lane are kept in a 64-bit mask");
+
+__global__ __launch_bounds__(kRankThreads) void allocate_ranked(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out,
+                                                                int sink, int bucket_shift, int32_t *out_idx,
+                                                                int32_t *out_count)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t *table = (uint32_t *)smem;  // kHashSlots
+    uint32_t *sel = table + kHashSlots;  // ILRE_MAX_BUDGET tokens, then as many again for the final sort
+    __shared__ uint32_t wsum[kRankWaves];
+    __shared__ uint32_t wfree[2][kRankWaves];  // free tokens per wavefront, two generations
+    __shared__ uint32_t c_share[ILRE_MAX_POOL_KERNELS], c_tokens[ILRE_MAX_POOL_KERNELS];
+
+    for (int i = threadIdx.x; i < kHashSlots; i += kRankThreads) table[i] = kEmpty;
+    if ((int)threadIdx.x < n) {
+        c_share[threadIdx.x] = ctrl[threadIdx.x].share;
+        c_tokens[threadIdx.x] = ctrl[threadIdx.x].total_n * ctrl[threadIdx.x].cell;  // <= kCandCap by the host's limits
     }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < nsel; i += kThreads) atomicAdd(&cnt[sel[i] >> bucket_shift], 1u);
-    __syncthreads();
-    {
-        constexpr int BPT = kBuckets / kThreads;
-        uint32_t own[BPT], sum = 0;
-#pragma unroll
-        for (int k = 0; k < BPT; ++k) {
-            own[k] = cnt[threadIdx.x * BPT + k];
-            sum += own[k];
+    // At most (shares before j) tokens are allocated when combination j runs, so its B_j free tokens
+    // are among its first (shares up to and including j) ranked ones: the rest is never looked at.
+    if (threadIdx.x == 0) {
+        uint32_t upto = 0;
+        for (int j = 0; j < n; ++j) {
+            upto += c_share[j];
+            if (upto < c_tokens[j]) c_tokens[j] = upto;
         }
-        uint32_t total;
-        uint32_t run = block_scan_inclusive(sum, wsum, total) - sum;
+    }
+    __syncthreads();
+
+    // Loads are unconditional from a clamped slot of the list's storage, so that all are in flight
+    // together; a whole group of kRankG tokens a lane is fetched when any of it is needed.
+    auto fetch = [&](int j, uint32_t(&raw)[kRankPer]) {
+        const uint32_t *list = (const uint32_t *)(cand + (size_t)j * kCandCap);
+        const uint32_t per = (c_tokens[j] + kRankThreads - 1) / kRankThreads;
+        const uint32_t base = (uint32_t)wave * per * 64u + (uint32_t)lane;
 #pragma unroll
-        for (int k = 0; k < BPT; ++k) {
-            start[threadIdx.x * BPT + k] = run;
-            run += own[k];
+        for (int g = 0; g < kRankGroups; ++g) {
+            if ((uint32_t)(g * kRankG) < per) {  // uniform
+#pragma unroll
+                for (int u = 0; u < kRankG; ++u) {
+                    const uint32_t r = base + 64u * (g * kRankG + u);
+                    raw[g * kRankG + u] = list[r < (uint32_t)kCandCap ? r : (uint32_t)kCandCap - 1u];
+                }
+            }
         }
+    };
+
+    uint32_t tok[kRankPer], nxt[kRankPer];
+    if (n > 0) fetch(0, nxt);
+    uint32_t nsel = 0;
+    int gen = 0;
+    for (int j = 0; j < n; ++j) {
+#pragma unroll
+        for (int i = 0; i < kRankPer; ++i) tok[i] = nxt[i];
+        if (j + 1 < n) fetch(j + 1, nxt);
+        uint32_t share = c_share[j];
+        if ((uint32_t)n_out - nsel < share) share = (uint32_t)n_out - nsel;
+        if (share == 0) continue;  // uniform
+        const uint32_t cn = c_tokens[j];
+        const uint32_t per = (cn + kRankThreads - 1) / kRankThreads;
+        const uint32_t base = (uint32_t)wave * per * 64u + (uint32_t)lane;
+
+        // Per group: the hash-set probes of all its tokens advance together, one round of LDS reads
+        // per step of the longest probe chain, then the wavefront's count by ballots.
+        uint64_t free_bits = 0;
+        uint32_t run = 0;
+#pragma unroll
+        for (int g = 0; g < kRankGroups; ++g) {
+            if ((uint32_t)(g * kRankG) < per) {  // uniform
+                uint32_t slot[kRankG];
+                uint32_t pend = 0;
+#pragma unroll
+                for (int u = 0; u < kRankG; ++u) {
+                    const int i = g * kRankG + u;
+                    slot[u] = hash_slot(tok[i]);
+                    if ((uint32_t)i < per && base + 64u * i < cn) pend |= 1u << u;
+                }
+                while (__any(pend != 0)) {
+                    uint32_t seen_tok[kRankG];
+#pragma unroll
+                    for (int u = 0; u < kRankG; ++u) seen_tok[u] = table[slot[u]];
+#pragma unroll
+                    for (int u = 0; u < kRankG; ++u) {
+                        if ((pend >> u) & 1u) {
+                            if (seen_tok[u] == kEmpty) {
+                                free_bits |= 1ull << (g * kRankG + u);
+                                pend &= ~(1u << u);
+                            } else if (seen_tok[u] == tok[g * kRankG + u]) {
+                                pend &= ~(1u << u);
+                            } else {
+                                slot[u] = (slot[u] + 1) & (kHashSlots - 1);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kRankG; ++u) run += (uint32_t)__popcll(__ballot((free_bits >> (g * kRankG + u)) & 1ull));
+            }
+        }
+        if (lane == 0) wfree[gen][wave] = run;
+        lds_barrier();
+        uint32_t before = 0, total_free = 0;
+#pragma unroll
+        for (int w = 0; w < kRankWaves; ++w) {
+            const uint32_t c = wfree[gen][w];
+            if (w < wave) before += c;
+            total_free += c;
+        }
+        gen ^= 1;
+        const uint32_t take = share < total_free ? share : total_free;
+        const uint32_t quota = take > before ? take - before : 0u;  // of this wavefront's free tokens, in rank order
+        uint32_t seen = 0;
+#pragma unroll
+        for (int g = 0; g < kRankGroups; ++g) {
+            if ((uint32_t)(g * kRankG) < per && seen < quota) {  // uniform
+#pragma unroll
+                for (int u = 0; u < kRankG; ++u) {
+                    const int i = g * kRankG + u;
+                    const bool fr = (free_bits >> i) & 1ull;
+                    const uint64_t mask = __ballot(fr);
+                    const uint32_t pos = seen + (uint32_t)__popcll(mask & lanes_below);
+                    if (fr && pos < quota) {
+                        sel[nsel + before + pos] = tok[i];
+                        mark_allocated(table, tok[i]);
+                    }
+                    seen += (uint32_t)__popcll(mask);
+                }
+            }
+        }
+        nsel += take;
+        lds_barrier();  // the set is complete before the next combination probes it
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < nsel; i += kThreads) {
-        const uint32_t t = sel[i], bkt = t >> bucket_shift;
-        grp[start[bkt] + atomicAdd(&fill[bkt], 1u)] = t;
-    }
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < nsel; i += kThreads) {
-        const uint32_t t = grp[i], bkt = t >> bucket_shift;
-        const uint32_t s0 = start[bkt], s1 = s0 + cnt[bkt];
-        uint32_t rank = s0;
-        for (uint32_t q = s0; q < s1; ++q) rank += grp[q] < t ? 1u : 0u;
-        out_idx[sink + rank] = (int32_t)(t + sink);
-    }
-    for (int i = threadIdx.x; i < sink; i += kThreads) out_idx[i] = i;
-    for (int i = nsel + threadIdx.x; i < n_out; i += kThreads) out_idx[sink + i] = -1;
-    if (threadIdx.x == 0 && out_count) *out_count = sink + (int32_t)nsel;
+    emit_ascending<kRankThreads>(table, sel, wsum, nsel, n_out, sink, bucket_shift, out_idx, out_count);
 }
 
 }  // namespace
@@ -831,10 +1046,18 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
     int bucket_shift = 0;
     while (((int64_t)kBuckets << bucket_shift) < L) ++bucket_shift;
 
+    // Dynamic LDS ceilings are the same constants on every call (idempotent, so concurrent callers agree).
+    constexpr int kPoolLdsMax = kPoolWaves * 2 * (kSelFine + 2 * (ILRE_MAX_AVG_KERNEL > ILRE_MAX_POOL_KERNEL ? ILRE_MAX_AVG_KERNEL : ILRE_MAX_POOL_KERNEL)) * (int)sizeof(float);
+    constexpr int kSortLdsMax = 16384 * (int)sizeof(uint64_t);  // >= ILRE_MAX_BUDGET + 1 keys, padded to a power of two
     hipError_t e;
     if ((e = hipFuncSetAttribute((const void *)allocate, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)allocate_ranked, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)pool_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)refine, hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsMax)) != hipSuccess) return e;
     if (L == 0) {  // nothing but the sink part
-        hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, 0, 0, job.sink, 0, out_idx, out_count);
+        hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, 0, 0, job.sink, 0, out_idx, out_count);
         return hipGetLastError();
     }
 
@@ -883,21 +1106,25 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
         if (len > len_max) len_max = len;
     }
     cp.n = job.n_max;
+    uint32_t sort_n = 0;  // printed form: candidates are sorted in LDS, padded to a power of two
+    if (job.mode == kSelMaxAvg) {
+        sort_n = 2;
+        for (int j = 0; j < n; ++j)
+            while (sort_n < prm.want[j]) sort_n *= 2;
+    }
     const float *vals = job.mode == kSelMaxAvg ? cells : scores;
     const uint32_t nfine = (uint32_t)((len_max + kSelFine - 1) / kSelFine);
     const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)(kSelFine + halo_max) * sizeof(float);
     // Workgroups per combination in the pooling passes; beyond the cap the wavefronts loop over the
-    // entries.  The histogram passes end with one atomic per hot bin and workgroup on a handful of
-    // addresses (about 13 ns each, serialised), so they use fewer, longer-running workgroups.
+    // entries.  A histogram workgroup carries fixed work (clearing and flushing 2048 bins, one atomic per
+    // hot bin on a handful of addresses, about 13 ns each and serialised, the completion counter), so
+    // those passes aim at about one resident round of workgroups over all combinations.
     auto pool_blocks = [](uint32_t entries, uint32_t cap) {
         const uint32_t want = (entries + kPoolWaves - 1) / kPoolWaves;
         return want < cap ? (want ? want : 1u) : cap;
     };
-    constexpr uint32_t kHistCap = 256, kCollectCap = 1024;
-
-    if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)pool_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pool_lds)) != hipSuccess) return e;
+    auto clamp_u32 = [](uint32_t x, uint32_t lo, uint32_t hi) { return x < lo ? lo : (x > hi ? hi : x); };
+    constexpr uint32_t kHistGrid = 2560, kCollectGrid = 8192;
 
     Entries ent{nullptr, nullptr};
     uint32_t entries = nfine;
@@ -931,14 +1158,18 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
         // pruning rule is meant for (a few times the budget) and let the wavefronts loop
         entries = 4u * (uint32_t)n_out + 1024u;
     }
-    const uint32_t hblocks = pool_blocks(entries, kHistCap), cblocks = pool_blocks(entries, kCollectCap);
+    const uint32_t hcap = clamp_u32(kHistGrid / (uint32_t)n, 32u, 256u), ccap = clamp_u32(kCollectGrid / (uint32_t)n, 64u, 1024u);
+    const uint32_t hblocks = pool_blocks(entries, hcap), cblocks = pool_blocks(entries, ccap);
 
     hipLaunchKernelGGL(sel_init, dim3(n), dim3(kThreads), 0, s, prm, hist, ctrl, done);
     hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, vals, n, ctrl, hist, done, ent);
     hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, vals, n, ctrl, hist, done, ent);
     hipLaunchKernelGGL(collect, dim3(cblocks, n), dim3(kPoolThreads), pool_lds, s, vals, ctrl, cand, tie, ent);
-    hipLaunchKernelGGL(refine, dim3(n), dim3(kThreads), 0, s, ctrl, cand, tie);
-    hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n, n_out, job.sink, bucket_shift, out_idx, out_count);
+    hipLaunchKernelGGL(refine, dim3(n), dim3(kThreads), (size_t)sort_n * sizeof(uint64_t), s, ctrl, cand, tie, sort_n);
+    if (job.mode == kSelMaxAvg)
+        hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, n, n_out, job.sink, bucket_shift, out_idx, out_count);
+    else
+        hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n, n_out, job.sink, bucket_shift, out_idx, out_count);
     return hipGetLastError();
 }
 

@@ -55,6 +55,34 @@ def index_set_report(gpu_idx: np.ndarray, oracle_scores: np.ndarray, pool_kernel
             "n_gpu": len(gpu_idx), "n_oracle": len(want)}
 
 
+def index_set_report_max_avg(gpu_idx: np.ndarray, oracle_scores: np.ndarray, max_kernels, avg_kernels, budget: int,
+                             sink: int):
+    """The same rule for Algorithm 1 as printed: a token in the symmetric difference is excused when, for
+    some combination, the oracle's average of its cell lies within 2*(ABS_TOL + REL_TOL*thr) of thr = the value
+    of the last cell that combination admitted from, or of its K_m-th ranked cell (the candidate cap)."""
+    s32 = oracle_scores.astype(np.float32)
+    want = oracle.allocate_max_avg(s32, max_kernels, avg_kernels, budget, sink=sink)
+    g = set(int(x) for x in gpu_idx.tolist())
+    o = set(int(x) for x in want.tolist())
+    diff = sorted(g ^ o)
+    unexcused = []
+    if diff:
+        th = oracle.thresholds_max_avg(s32, max_kernels, avg_kernels, budget, sink=sink)
+        for t in diff:
+            ok = False
+            for per_token, last, cap in th:
+                v = per_token[t]
+                if np.isnan(v):
+                    continue
+                for thr in (last, cap):
+                    if thr is not None and abs(v - thr) <= 2 * (ABS_TOL + REL_TOL * abs(thr)):
+                        ok = True
+            if not ok:
+                unexcused.append(t)
+    return {"sym_diff": len(diff), "excused": len(diff) - len(unexcused), "unexcused": unexcused,
+            "n_gpu": len(gpu_idx), "n_oracle": len(want)}
+
+
 def check_index_structure(idx: np.ndarray, L: int, budget: int):
     assert idx.shape == (min(budget, L),)
     assert idx.dtype == np.int32

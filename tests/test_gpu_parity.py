@@ -9,7 +9,8 @@ import torch
 import inputs
 import oracle
 import paper_2508_17892_amd as il
-from parity import ABS_TOL, REL_TOL, check_index_structure, index_set_report, score_errors, to_device
+from parity import (ABS_TOL, REL_TOL, check_index_structure, index_set_report, index_set_report_max_avg, score_errors,
+                    to_device)
 
 pytestmark = pytest.mark.gpu
 
@@ -225,6 +226,53 @@ def test_end_to_end_ragged_bf16():
     inp = inputs.custom(L=9001, Lq=40, Hq=16, Hkv=4, d=128, dtype="bf16", n_spans=3, span_len=(16, 40),
                         channel_scale=True, seed=77)
     _end_to_end(inp, (1, 3, 7, 15, 31), 512)
+
+
+def _end_to_end_max_avg(inp, mk, ak, budget, sink):
+    """Whole path with Algorithm 1 as printed: scores within tolerance of the oracle's, bit-identical to
+    the window-max entry point's (same scoring kernels), indices equal to the staged call on those scores,
+    and equal to the oracle's set up to tokens at a combination's threshold."""
+    q, k = to_device(inp.q), to_device(inp.k)
+    idx, count, scores = il.ilre_recall_max_avg(q, k, budget, mk, ak, sink)
+    _, ref_scores = il.ilre_recall(q, k, min(budget, 64), (3,))
+    staged_idx, staged_count = il.ilre_select_max_avg(scores, budget, mk, ak, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, ref_scores)
+    assert torch.equal(idx, staged_idx) and int(count.item()) == int(staged_count.item())
+    n = int(count.item())
+    idx, scores = idx.cpu().numpy(), scores.cpu().numpy()
+    want_scores, _, _ = oracle.scores(inp.q, inp.k)
+    bad, worst = score_errors(scores, want_scores)
+    assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
+    assert (idx[:sink] == np.arange(sink)).all() and (np.diff(idx[:n].astype(np.int64)) > 0).all()
+    assert (idx[n:] == -1).all() and idx[:n].max() < inp.workload.L
+    rep = index_set_report_max_avg(idx[:n], want_scores, mk, ak, budget, sink)
+    assert not rep["unexcused"], rep
+    return idx[:n], rep
+
+
+def test_end_to_end_max_avg_cfg1():
+    _announce("end_to_end max/avg cfg1 (paper default pooling set, sink 4)")
+    inp = inputs.config(1)
+    idx, rep = _end_to_end_max_avg(inp, PAPER_MAX, PAPER_AVG, inp.workload.budget, 4)
+    mask = inp.needle_mask
+    assert mask[idx].sum() >= 0.95 * mask.sum()
+
+
+def test_end_to_end_max_avg_cfg2():
+    _announce("end_to_end max/avg cfg2 (paper default pooling set, sink 4)")
+    inp = inputs.config(2)
+    idx, rep = _end_to_end_max_avg(inp, PAPER_MAX, PAPER_AVG, inp.workload.budget, 4)
+    mask = inp.needle_mask
+    assert mask[idx].sum() >= 0.95 * mask.sum()
+
+
+def test_end_to_end_max_avg_ragged_bf16():
+    _announce("end_to_end max/avg ragged bf16")
+    inp = inputs.custom(L=9001, Lq=40, Hq=16, Hkv=4, d=128, dtype="bf16", n_spans=3, span_len=(16, 40),
+                        channel_scale=True, seed=77)
+    _end_to_end_max_avg(inp, (4,), (5,), 512, 0)          # the paper's One-Max-Avg ablation setting
+    _end_to_end_max_avg(inp, PAPER_MAX, tuple(range(1, 10)), 1000, 4)   # Less-Avg-Kernels
 
 
 def test_token_major_strides():

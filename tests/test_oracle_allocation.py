@@ -167,3 +167,27 @@ def test_max_avg_structure():
     s = rng.random(5000).astype(np.float32)
     idx = oracle.allocate_max_avg(s, [2, 4, 8], list(range(1, 17)), 480, sink=4)
     assert idx[:4].tolist() == [0, 1, 2, 3] and (np.diff(idx) > 0).all() and len(idx) <= 4 + 480 and idx.max() < 5000
+
+
+def test_thresholds_max_avg_replay():
+    """The replay used by the index-set comparison rule agrees with allocate_max_avg: every admitted token's
+    value in some combination is at or above what that combination last admitted, and nothing below a
+    combination's cap value was ever a candidate of it."""
+    rng = np.random.default_rng(5)
+    s = rng.random(4000).astype(np.float32)
+    mk, ak, B, sink = [2, 4, 8], [1, 2, 3, 8], 600, 4
+    idx = oracle.allocate_max_avg(s, mk, ak, B, sink=sink)
+    th = oracle.thresholds_max_avg(s, mk, ak, B, sink=sink)
+    assert len(th) == len(mk) * len(ak)
+    for per_token, last, cap in th:
+        assert per_token.shape == (4000,) and np.isnan(per_token[:sink]).all()
+        assert last is not None and cap is not None and last >= cap
+    body = idx[idx >= sink]
+    admitted_somewhere = np.zeros(len(body), dtype=bool)
+    for per_token, last, cap in th:
+        admitted_somewhere |= per_token[body] >= last
+    assert admitted_somewhere.all()
+    # m = 4: tokens after the last whole cell have no value in that combination
+    th2 = oracle.thresholds_max_avg(s[:1003], [4], [1], 50, sink=0)
+    assert np.isnan(th2[0][0][1000:]).all() and not np.isnan(th2[0][0][:1000]).any()
+    assert th2[0][2] == float(np.sort(s[:1000].reshape(250, 4).max(axis=1))[::-1][50 // 4])
