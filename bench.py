@@ -41,6 +41,8 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE in rocprofv3 --pmc runs of this script")
     ap.add_argument("--no-select-scaled", action="store_true",
                     help="skip the scaled selection leg (ilre_select on 2^27 synthetic scores, HBM roofline)")
+    ap.add_argument("--no-paper-allocation", action="store_true",
+                    help="skip the leg that times the whole step with Algorithm 1 as printed (48 max/average combinations)")
     ap.add_argument("--gemm-context", action="store_true",
                     help="also time a library bf16 GEMM (8192^3, random operands) as context for the MFMA roofline")
     args = ap.parse_args()
@@ -134,6 +136,39 @@ def main() -> int:
                          "col_scores": round(flops_per_pass / stage_ms[1] / 1e9, 1)},
         "roofline": roofline,
     }
+
+    if not args.no_paper_allocation:
+        # The same step with Algorithm 1 as printed (strided max pooling x average pooling, the paper's
+        # default 3 x 16 combinations, K_m cap, sink 4) in place of the window-max form.
+        mk, ak, sink = (2, 4, 8), tuple(range(1, 17)), 4
+        ws_p = il.alloc_workspace_max_avg(wl.L, wl.Lq, wl.Hq, wl.Hkv, wl.d, sink, mk, len(ak), dt)
+        p_idx = torch.empty(sink + min(budget, wl.L - sink), dtype=torch.int32, device="cuda")
+        p_cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+
+        def paper_step():
+            il.ilre_recall_max_avg(q, k, budget, mk, ak, sink, workspace=ws_p, out_idx=p_idx, out_count=p_cnt,
+                                   out_scores=out_scores)
+
+        for _ in range(args.warmup):
+            paper_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            paper_step()
+        torch.cuda.synchronize()
+        p_wall = time.perf_counter() - t0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            il.ilre_select_max_avg(out_scores, budget, mk, ak, sink, workspace=ws_p, out_idx=p_idx, out_count=p_cnt)
+        e1.record()
+        torch.cuda.synchronize()
+        result["paper_allocation"] = {"max_kernels": list(mk), "avg_kernels": list(ak), "sink": sink,
+                                      "ms_per_step": round(p_wall * 1e3 / args.steps, 4),
+                                      "tokens_per_s": round(wl.L * args.steps / p_wall, 1),
+                                      "select_ms": round(e0.elapsed_time(e1) / args.steps, 4),
+                                      "kept": int(p_cnt.item())}
+        del ws_p
 
     if not args.no_select_scaled:
         # At the listed workloads the score vector (<= 4 MiB) is cache resident and the selection
