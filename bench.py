@@ -41,6 +41,7 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE in rocprofv3 --pmc runs of this script")
     ap.add_argument("--no-select-scaled", action="store_true",
                     help="skip the scaled selection leg (ilre_select on 2^27 synthetic scores, HBM roofline)")
+    ap.add_argument("--no-rerope", action="store_true", help="skip the leg that times the DCA re-RoPE of the key cache")
     ap.add_argument("--no-paper-allocation", action="store_true",
                     help="skip the leg that times the whole step with Algorithm 1 as printed (48 max/average combinations)")
     ap.add_argument("--gemm-context", action="store_true",
@@ -169,6 +170,26 @@ def main() -> int:
                                       "select_ms": round(e0.elapsed_time(e1) / args.steps, 4),
                                       "kept": int(p_cnt.item())}
         del ws_p
+
+    if not args.no_rerope:
+        # DCA on: the key cache is re-RoPE'd once before the recall step (second DCA equation), one
+        # streaming pass; prefill chunks of 1024 tokens, the first with the 4 sink tokens, Llama-3.1 base.
+        k_rot = torch.empty_like(k)
+        il.ilre_rerope_keys(k, 1024, 4, rope_base=500000.0, out=k_rot)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            il.ilre_rerope_keys(k, 1024, 4, rope_base=500000.0, out=k_rot)
+        e1.record()
+        torch.cuda.synchronize()
+        r_ms = e0.elapsed_time(e1) / args.steps
+        r_bytes = 2.0 * k.numel() * k.element_size()
+        result["rerope"] = {"chunk_tokens": 1024, "first_extra": 4, "rope_base": 500000.0, "ms": round(r_ms, 4),
+                            "algorithmic_bytes": r_bytes, "bound": "hbm", "achieved": round(r_bytes / (r_ms * 1e-3) / 1e9, 1),
+                            "peak": 8000.0, "unit": "GB/s", "frac": round(r_bytes / (r_ms * 1e-3) / 1e9 / 8000.0, 4),
+                            "note": "ilre_rerope_keys on the same key cache, out of place: every key read once, written once"}
+        del k_rot
 
     if not args.no_select_scaled:
         # At the listed workloads the score vector (<= 4 MiB) is cache resident and the selection

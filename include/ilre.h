@@ -61,6 +61,8 @@ typedef enum {
 
 typedef enum { ILRE_F32 = 0, ILRE_BF16 = 1 } ilre_dtype;
 typedef enum { ILRE_SCORE_SUM = 0, ILRE_SCORE_MAX = 1 } ilre_score_mode;
+/* which elements of a key vector form rotary pair j: (x[j], x[j + d/2]) or (x[2j], x[2j+1]) */
+typedef enum { ILRE_ROPE_HALF = 0, ILRE_ROPE_INTERLEAVED = 1 } ilre_rope_pairing;
 
 /* ilre_row_stats / ilre_recall: follow the running row maximum over the whole context, so that the
    reference written to row_ref is exactly max_t logit (a few percent slower).  Without it the
@@ -160,6 +162,22 @@ int ilre_recall_max_avg(const void *q, const void *k_cache,
 int ilre_workspace_bytes_max_avg(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d, int32_t sink,
                                  const int32_t *max_kernels, int32_t n_max, int32_t n_avg,
                                  int32_t dtype, size_t *out_bytes);
+
+/* DCA re-RoPE of the retrieval layer's key cache (Section 3.3, second DCA equation), to be run before
+   the recall step when DCA is on.  The context is the sequence of prefill chunks 1..N_C: chunk 1 holds
+   first_extra + chunk_tokens tokens (the sink part rides with it), the others chunk_tokens, the last one
+   what is left; N_C = max(1, ceil((L - first_extra) / chunk_tokens)).  The keys of chunk i < N_C - 1 are
+   turned by R(D_i), D_i = (N_C - 1 - i) * chunk_tokens: pair j of a key vector (see ilre_rope_pairing)
+   goes from (x, y) to (x cos a - y sin a, y cos a + x sin a) with a = D_i * inv_freq[j], which moves a key
+   embedded at position p to p + D_i.  Chunks N_C - 1 and N_C are copied unchanged.  Angles are evaluated
+   in fp64, the rotation in fp32, the result is rounded to the cache's element type (nearest even).
+   k_in      dev  [Hkv, L, d], element type opts->dtype, layout by opts->k_stride_head / k_stride_token
+   k_out     dev  same shape, type and strides; may be k_in itself (in place), must not overlap it otherwise
+   inv_freq  host d/2 doubles, or NULL for rope_base^(-2j/d) (rope_base > 0)
+   Needs no workspace. */
+int ilre_rerope_keys(const void *k_in, void *k_out, int64_t L, int32_t Hkv, int32_t d,
+                     int32_t chunk_tokens, int32_t first_extra, double rope_base, const double *inv_freq,
+                     int32_t pairing, const ilre_opts *opts);
 
 /* Message for the last non-OK status returned to the calling thread (static storage, never NULL). */
 const char *ilre_last_error(void);

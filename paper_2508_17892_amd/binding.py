@@ -19,6 +19,7 @@ ILRE_OK, ILRE_EINVAL, ILRE_EUNSUPPORTED, ILRE_ENOMEM, ILRE_EHIP = range(5)
 ILRE_F32, ILRE_BF16 = 0, 1
 ILRE_SCORE_SUM, ILRE_SCORE_MAX = 0, 1
 ILRE_FLAG_EXACT_ROW_MAX = 1
+ILRE_ROPE_HALF, ILRE_ROPE_INTERLEAVED = 0, 1
 ILRE_MAX_BUDGET = 8192
 ILRE_MAX_POOL_KERNEL = 2047
 ILRE_MAX_POOL_KERNELS = 64
@@ -26,7 +27,8 @@ ILRE_MAX_MAX_KERNEL = 1024
 ILRE_MAX_AVG_KERNEL = 1024
 
 EXPORTS = ("ilre_workspace_bytes", "ilre_recall", "ilre_row_stats", "ilre_col_scores", "ilre_select",
-           "ilre_select_max_avg", "ilre_recall_max_avg", "ilre_workspace_bytes_max_avg", "ilre_last_error")
+           "ilre_select_max_avg", "ilre_recall_max_avg", "ilre_workspace_bytes_max_avg", "ilre_rerope_keys",
+           "ilre_last_error")
 
 
 class IlreOpts(ctypes.Structure):
@@ -83,6 +85,9 @@ def load() -> ctypes.CDLL:
         lib.ilre_workspace_bytes_max_avg.restype = ctypes.c_int
         lib.ilre_workspace_bytes_max_avg.argtypes = [i64, i32, i32, i32, i32, i32, pi, i32, i32, i32,
                                                      ctypes.POINTER(ctypes.c_size_t)]
+        lib.ilre_rerope_keys.restype = ctypes.c_int
+        lib.ilre_rerope_keys.argtypes = [vp, vp, i64, i32, i32, i32, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_double),
+                                         i32, po]
         lib.ilre_last_error.restype = ctypes.c_char_p
         lib.ilre_last_error.argtypes = []
         _lib = lib
@@ -289,3 +294,25 @@ def ilre_recall_max_avg(q: torch.Tensor, k_cache: torch.Tensor, budget: int, max
                                       len(avg_kernels), out_idx.data_ptr(), out_count.data_ptr(), out_scores.data_ptr(),
                                       ctypes.byref(o)))
     return out_idx, out_count, out_scores
+
+
+def ilre_rerope_keys(k_cache: torch.Tensor, chunk_tokens: int, first_extra: int = 0, *, rope_base: float = 10000.0,
+                     inv_freq: Optional[Sequence[float]] = None, pairing: int = ILRE_ROPE_HALF,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """DCA re-RoPE of a key cache [Hkv, L, d]; `out` may be k_cache itself (in place) and must share its strides."""
+    if k_cache.dim() != 3 or not k_cache.is_cuda or k_cache.stride(2) != 1:
+        raise ValueError("k_cache is a device tensor [Hkv, L, d] with the head dimension contiguous")
+    Hkv, L, d = k_cache.shape
+    if out is None:
+        out = torch.empty_strided(k_cache.shape, k_cache.stride(), dtype=k_cache.dtype, device=k_cache.device)
+    if out.shape != k_cache.shape or out.stride() != k_cache.stride() or out.dtype != k_cache.dtype:
+        raise ValueError("out must have the shape, strides and element type of k_cache")
+    o = _opts(_dtype_code(k_cache), 0, 0.0, ILRE_SCORE_SUM, None, None, k_cache)
+    freq = None
+    if inv_freq is not None:
+        if len(inv_freq) != d // 2:
+            raise ValueError("inv_freq must have d/2 entries")
+        freq = (ctypes.c_double * (d // 2))(*[float(x) for x in inv_freq])
+    _check(load().ilre_rerope_keys(k_cache.data_ptr(), out.data_ptr(), L, Hkv, d, int(chunk_tokens), int(first_extra),
+                                   float(rope_base), freq, int(pairing), ctypes.byref(o)))
+    return out

@@ -345,6 +345,43 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
 
 }  // namespace
 
+int ilre_rerope_keys(const void *k_in, void *k_out, int64_t L, int32_t Hkv, int32_t d, int32_t chunk_tokens,
+                     int32_t first_extra, double rope_base, const double *inv_freq, int32_t pairing, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, 1, Hkv, Hkv, d, opts->dtype))) return rc;
+    if (!k_in || !k_out) return fail(ILRE_EINVAL, "k_in or k_out is null");
+    if (Hkv > 65535) return fail(ILRE_EUNSUPPORTED, "more than 65535 kv heads");
+    if (chunk_tokens < 1 || first_extra < 0) return fail(ILRE_EINVAL, "chunk_tokens must be positive, first_extra non-negative");
+    if (pairing != ILRE_ROPE_HALF && pairing != ILRE_ROPE_INTERLEAVED) return fail(ILRE_EUNSUPPORTED, "unknown pairing %d", pairing);
+    if (!inv_freq && !(rope_base > 0.0 && isfinite(rope_base))) return fail(ILRE_EINVAL, "rope_base must be positive and finite");
+    const int es = opts->dtype == ILRE_BF16 ? 2 : 4;
+    ilre::RopeArgs a{};
+    a.in = (const unsigned char *)k_in;
+    a.out = (unsigned char *)k_out;
+    a.L = L;
+    a.Hkv = Hkv;
+    a.stride_token = opts->k_stride_token ? opts->k_stride_token : d;
+    a.stride_head = opts->k_stride_head ? opts->k_stride_head : L * (int64_t)d;
+    if (a.stride_token < d || a.stride_head < d) return fail(ILRE_EINVAL, "strides must be >= d (rows may not overlap)");
+    if ((a.stride_token * es) % 16 != 0 || (a.stride_head * es) % 16 != 0) return fail(ILRE_EINVAL, "strides must be multiples of 16 bytes");
+    if (((uintptr_t)k_in & 15) || ((uintptr_t)k_out & 15)) return fail(ILRE_EINVAL, "k_in and k_out must be 16-byte aligned");
+    a.chunk = chunk_tokens;
+    a.first_extra = first_extra;
+    const int64_t body = L - first_extra;
+    const int64_t nchunks = body > 0 ? (body + chunk_tokens - 1) / chunk_tokens : 1;
+    a.nchunks = (int)nchunks;
+    for (int j = 0; j < d / 2; ++j) {
+        const double f = inv_freq ? inv_freq[j] : pow(rope_base, -2.0 * j / d);
+        if (!isfinite(f)) return fail(ILRE_EINVAL, "inv_freq[%d] is not finite", j);
+        a.inv_freq[j] = f;
+    }
+    const hipError_t e = ilre::launch_rerope(a, opts->dtype, pairing, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "re-RoPE launch");
+    return ILRE_OK;
+}
+
 int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                 int32_t budget, const int32_t *pool_kernels, int32_t *out_idx, float *out_scores, const ilre_opts *opts)
 {

@@ -126,4 +126,18 @@ SelectLayout make_select_layout(const SelectJob &job);
 hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
                          void *workspace, const SelectLayout &lay, hipStream_t s);
 
+// ---------------------------------------------------------------- DCA re-RoPE of the key cache
+
+struct RopeArgs {
+    const unsigned char *in;
+    unsigned char *out;
+    int64_t L;
+    int Hkv;
+    int64_t stride_head, stride_token;  // in elements, the same for in and out
+    int chunk, first_extra, nchunks;
+    double inv_freq[ILRE_HEAD_DIM / 2];
+};
+
+hipError_t launch_rerope(const RopeArgs &a, int dtype, int pairing, hipStream_t s);
+
 }  // namespace ilre
