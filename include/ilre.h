@@ -163,6 +163,13 @@ int ilre_workspace_bytes_max_avg(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv,
                                  const int32_t *max_kernels, int32_t n_max, int32_t n_avg,
                                  int32_t dtype, size_t *out_bytes);
 
+/* Last line of Algorithm 1: the compressed prompt C[I], i.e. out[i] = input_ids[idx[i]] for the n entries
+   of an index list written by one of the selection entry points; entries that are -1 (unused slots of the
+   printed form) or out of range give -1.  input_ids: dev, L int32.  idx: dev, n int32.  out: dev, n int32
+   (must not overlap idx).  Needs no workspace; opts supplies the stream. */
+int ilre_gather_ids(const int32_t *input_ids, int64_t L, const int32_t *idx, int32_t n, int32_t *out,
+                    const ilre_opts *opts);
+
 /* DCA re-RoPE of the retrieval layer's key cache (Section 3.3, second DCA equation), to be run before
    the recall step when DCA is on.  The context is the sequence of prefill chunks 1..N_C: chunk 1 holds
    first_extra + chunk_tokens tokens (the sink part rides with it), the others chunk_tokens, the last one

@@ -28,7 +28,7 @@ ILRE_MAX_AVG_KERNEL = 1024
 
 EXPORTS = ("ilre_workspace_bytes", "ilre_recall", "ilre_row_stats", "ilre_col_scores", "ilre_select",
            "ilre_select_max_avg", "ilre_recall_max_avg", "ilre_workspace_bytes_max_avg", "ilre_rerope_keys",
-           "ilre_last_error")
+           "ilre_gather_ids", "ilre_last_error")
 
 
 class IlreOpts(ctypes.Structure):
@@ -88,6 +88,8 @@ def load() -> ctypes.CDLL:
         lib.ilre_rerope_keys.restype = ctypes.c_int
         lib.ilre_rerope_keys.argtypes = [vp, vp, i64, i32, i32, i32, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_double),
                                          i32, po]
+        lib.ilre_gather_ids.restype = ctypes.c_int
+        lib.ilre_gather_ids.argtypes = [vp, i64, vp, i32, vp, po]
         lib.ilre_last_error.restype = ctypes.c_char_p
         lib.ilre_last_error.argtypes = []
         _lib = lib
@@ -315,4 +317,16 @@ def ilre_rerope_keys(k_cache: torch.Tensor, chunk_tokens: int, first_extra: int 
         freq = (ctypes.c_double * (d // 2))(*[float(x) for x in inv_freq])
     _check(load().ilre_rerope_keys(k_cache.data_ptr(), out.data_ptr(), L, Hkv, d, int(chunk_tokens), int(first_extra),
                                    float(rope_base), freq, int(pairing), ctypes.byref(o)))
+    return out
+
+
+def ilre_gather_ids(input_ids: torch.Tensor, idx: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """C[I]: the input IDs (int32 device vector) of an index list; -1 where the list holds -1."""
+    if input_ids.dtype != torch.int32 or idx.dtype != torch.int32 or not input_ids.is_contiguous() or not idx.is_contiguous():
+        raise ValueError("input_ids and idx must be contiguous int32 device vectors")
+    if out is None:
+        out = torch.empty_like(idx)
+    o = _opts(ILRE_F32, 0, 0.0, ILRE_SCORE_SUM, None)
+    _check(load().ilre_gather_ids(input_ids.data_ptr(), input_ids.numel(), idx.data_ptr(), idx.numel(), out.data_ptr(),
+                                  ctypes.byref(o)))
     return out

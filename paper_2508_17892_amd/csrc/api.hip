@@ -345,6 +345,19 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
 
 }  // namespace
 
+int ilre_gather_ids(const int32_t *input_ids, int64_t L, const int32_t *idx, int32_t n, int32_t *out, const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if (L < 1 || L > 0x7FFFFFFFll) return fail(ILRE_EINVAL, "L must be in [1, 2^31)");
+    if (n < 0) return fail(ILRE_EINVAL, "n must be non-negative");
+    if (!input_ids || !idx || !out) return fail(ILRE_EINVAL, "input_ids, idx or out is null");
+    if (n == 0) return ILRE_OK;
+    const hipError_t e = ilre::launch_gather_ids(input_ids, L, idx, n, out, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "ID gather launch");
+    return ILRE_OK;
+}
+
 int ilre_rerope_keys(const void *k_in, void *k_out, int64_t L, int32_t Hkv, int32_t d, int32_t chunk_tokens,
                      int32_t first_extra, double rope_base, const double *inv_freq, int32_t pairing, const ilre_opts *opts)
 {

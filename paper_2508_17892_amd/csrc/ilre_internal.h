@@ -126,6 +126,8 @@ SelectLayout make_select_layout(const SelectJob &job);
 hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
                          void *workspace, const SelectLayout &lay, hipStream_t s);
 
+hipError_t launch_gather_ids(const int32_t *ids, int64_t L, const int32_t *idx, int n, int32_t *out, hipStream_t s);
+
 // ---------------------------------------------------------------- DCA re-RoPE of the key cache
 
 struct RopeArgs {

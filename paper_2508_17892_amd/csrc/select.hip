@@ -980,7 +980,23 @@ __global__ __launch_bounds__(kRankThreads) void allocate_ranked(const SelCtrl *c
     emit_ascending<kRankThreads>(table, sel, wsum, nsel, n_out, sink, bucket_shift, out_idx, out_count);
 }
 
+// Last line of Algorithm 1: the input IDs of the allocated tokens, C[I].  Unused index slots (-1) give -1.
+__global__ __launch_bounds__(kPoolThreads) void gather_ids_kernel(const int32_t *ids, int64_t L, const int32_t *idx, int n,
+                                                                  int32_t *out)
+{
+    const int i = blockIdx.x * kPoolThreads + threadIdx.x;
+    if (i >= n) return;
+    const int32_t t = idx[i];
+    out[i] = (t >= 0 && t < L) ? ids[t] : -1;
+}
+
 }  // namespace
+
+hipError_t launch_gather_ids(const int32_t *ids, int64_t L, const int32_t *idx, int n, int32_t *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(gather_ids_kernel, dim3((n + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, ids, L, idx, n, out);
+    return hipGetLastError();
+}
 
 // Elements of combination j's source array and the tokens one element stands for.
 static void combo_shape(const SelectJob &job, int j, int64_t &len, int &cell)

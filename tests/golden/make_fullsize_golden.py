@@ -4,7 +4,8 @@
 For the workloads too large for the oracle to run inside a GPU test, the oracle is run once here and
 a compact digest is stored: sampled softmax row statistics, sampled per-token scores, the score total,
 the recalled index set, each kernel's admission threshold and the tokens the comparison rule excuses
-(oracle pooled score within 2*(1e-6 + 1e-3*thr_j) of a threshold).  Usage:
+(oracle pooled score within 2*(1e-6 + 1e-3*thr_j) of a threshold), and the same pair (index set, excused
+tokens) for Algorithm 1 as printed with the paper's default pooling set.  Usage:
 
     python tests/golden/make_fullsize_golden.py 3 4 5
 """
@@ -25,6 +26,7 @@ import oracle  # noqa: E402
 
 REL_TOL, ABS_TOL = 1e-3, 1e-6
 N_ROWS, N_RANDOM_TOKENS, N_SELECTED_TOKENS = 256, 1024, 1024
+PAPER_MAX, PAPER_AVG, PAPER_SINK = (2, 4, 8), tuple(range(1, 17)), 4   # default pooling set and sink size of the paper
 
 
 def digest(cfg: int) -> dict:
@@ -42,6 +44,15 @@ def digest(cfg: int) -> dict:
         thr_list.append(thr)
         if thr is not None:
             excused |= np.abs(pooled.astype(np.float64) - thr) <= 2 * (ABS_TOL + REL_TOL * abs(thr))
+    # Algorithm 1 as printed on the same scores: index set and the tokens its comparison rule excuses
+    # (cell average within tolerance of what a combination last admitted or of its K_m-th ranked cell)
+    ma_idx = oracle.allocate_max_avg(s32, PAPER_MAX, PAPER_AVG, wl.budget, sink=PAPER_SINK)
+    ma_excused = np.zeros(wl.L, dtype=bool)
+    for per_token, last, cap in oracle.thresholds_max_avg(s32, PAPER_MAX, PAPER_AVG, wl.budget, sink=PAPER_SINK):
+        for thr in (last, cap):
+            if thr is not None:
+                with np.errstate(invalid="ignore"):
+                    ma_excused |= np.abs(per_token - thr) <= 2 * (ABS_TOL + REL_TOL * abs(thr))
     rng = np.random.default_rng(3000 + cfg)
     rows = np.sort(rng.choice(wl.Hq * wl.Lq, size=N_ROWS, replace=False))
     toks = np.unique(np.concatenate([rng.choice(wl.L, size=N_RANDOM_TOKENS, replace=False),
@@ -65,6 +76,9 @@ def digest(cfg: int) -> dict:
         "indices": idx.tolist(),
         "thresholds": thr_list,
         "excused_tokens": np.flatnonzero(excused).tolist(),
+        "max_avg": {"max_kernels": list(PAPER_MAX), "avg_kernels": list(PAPER_AVG), "sink": PAPER_SINK,
+                    "indices": ma_idx.tolist(), "excused_tokens": np.flatnonzero(ma_excused).tolist(),
+                    "needle_recall": float(mask[ma_idx].sum() / max(1, mask.sum()))},
         "needle_tokens": int(mask.sum()),
         "needle_recall": float(mask[idx].sum() / max(1, mask.sum())),
         "precision_within_15_of_a_span": float(near[idx].mean()),

@@ -67,3 +67,31 @@ def test_fullsize_against_oracle_digest(cfg, golden_dir):
     assert not unexcused, f"{len(unexcused)} unexcused index differences, e.g. {unexcused[:8]}"
     print(f"[case] fullsize cfg{cfg}: worst score error {worst:.3f} of tolerance, index sym diff {len(diff)} (all excused)",
           flush=True)
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_fullsize_printed_allocation_against_oracle_digest(cfg, golden_dir):
+    """Algorithm 1 as printed (the paper's default pooling set, sink 4) on the full-size workloads:
+    index set equal to the oracle's up to the tokens its threshold rule excuses."""
+    g = _load(golden_dir, cfg)
+    if "max_avg" not in g:
+        pytest.skip("digest written before the printed form was added")
+    ma = g["max_avg"]
+    print(f"[case] fullsize printed allocation cfg{cfg} L={g['L']}", flush=True)
+    wl = inputs.CONFIGS[cfg]
+    inp = inputs.generate(wl)
+    q, k = to_device(inp.q), to_device(inp.k)
+    del inp
+    idx, count, scores = il.ilre_recall_max_avg(q, k, wl.budget, ma["max_kernels"], ma["avg_kernels"], ma["sink"])
+    torch.cuda.synchronize()
+    n = int(count.item())
+    idx = idx.cpu().numpy()
+    assert (idx[n:] == -1).all() and (np.diff(idx[:n].astype(np.int64)) > 0).all()
+    assert idx[:ma["sink"]].tolist() == list(range(ma["sink"]))
+    toks = np.array(g["tokens"])
+    bad, worst = score_errors(scores.cpu().numpy()[toks], np.array(g["token_scores"]))
+    assert bad == 0, worst
+    diff = set(idx[:n].tolist()) ^ set(ma["indices"])
+    unexcused = sorted(diff - set(ma["excused_tokens"]))
+    assert not unexcused, f"{len(unexcused)} unexcused index differences, e.g. {unexcused[:8]}"
+    print(f"[case] fullsize printed allocation cfg{cfg}: kept {n}, index sym diff {len(diff)} (all excused)", flush=True)

@@ -275,6 +275,23 @@ def test_end_to_end_max_avg_ragged_bf16():
     _end_to_end_max_avg(inp, PAPER_MAX, tuple(range(1, 10)), 1000, 4)   # Less-Avg-Kernels
 
 
+def test_gather_ids_is_the_compressed_prompt():
+    """Last line of Algorithm 1, C[I]: by definition the input IDs at the returned indices."""
+    _announce("gather ids")
+    rng = np.random.default_rng(17)
+    # a normal selection, and one whose candidates run out (21 tokens, cells of 8: 16 reachable, budget 20)
+    for L, budget, mk, ak, sink, short in ((50000, 3000, (2, 4, 8), (1, 2, 3), 4, False), (21, 20, (8,), (1,), 0, True)):
+        ids = rng.integers(0, 128256, size=L).astype(np.int32)
+        s = _scores_for("needles", L, rng) if L > 300 else rng.random(L).astype(np.float32)
+        idx, count = il.ilre_select_max_avg(torch.from_numpy(s).cuda(), budget, mk, ak, sink)
+        got = il.ilre_gather_ids(torch.from_numpy(ids).cuda(), idx)
+        torch.cuda.synchronize()
+        idx_h, n = idx.cpu().numpy(), int(count.item())
+        assert (n < idx_h.size) == short and (idx_h[n:] == -1).all()
+        want = np.where(idx_h >= 0, ids[np.clip(idx_h, 0, L - 1)], -1)
+        assert got.cpu().numpy().tolist() == want.tolist()
+
+
 def test_token_major_strides():
     _announce("token-major strided K and strided Q")
     inp = inputs.custom(L=2500, Lq=16, Hq=8, Hkv=2, d=128, dtype="bf16", n_spans=1, span_len=(16, 16), seed=5)
