@@ -100,3 +100,46 @@ def test_argument_errors_need_no_device():
     assert lib.ilre_col_scores(fake, fake, 1000, 8, 8, 2, 128, fake, fake, None, ctypes.byref(o)) == il.ILRE_EINVAL
     assert lib.ilre_select(None, 1000, 64, kern, fake, ctypes.byref(o)) == il.ILRE_EINVAL
     assert lib.ilre_select(fake, 1000, 64, kern, fake, ctypes.byref(o)) == il.ILRE_ENOMEM
+
+
+def test_argument_errors_of_the_printed_form_rerope_and_gather():
+    lib = il.load()
+    fake = ctypes.c_void_p(4096)          # never dereferenced: every call below fails validation first
+    o = _opts()
+    mk, ak = (ctypes.c_int32 * 3)(2, 4, 8), (ctypes.c_int32 * 2)(1, 5)
+
+    def sel(L=1000, sink=4, budget=64, mk_=mk, n_max=3, ak_=ak, n_avg=2, scores=fake, out=fake, opts=o):
+        return lib.ilre_select_max_avg(scores, L, sink, budget, mk_, n_max, ak_, n_avg, out, None, ctypes.byref(opts))
+
+    assert sel() == il.ILRE_ENOMEM                                   # everything valid except the missing workspace
+    assert sel(scores=None) == il.ILRE_EINVAL
+    assert sel(sink=-1) == il.ILRE_EINVAL and sel(sink=1001) == il.ILRE_EINVAL
+    assert sel(budget=0) == il.ILRE_EINVAL
+    assert sel(n_max=0) == il.ILRE_EINVAL and sel(ak_=None) == il.ILRE_EINVAL
+    assert sel(mk_=(ctypes.c_int32 * 3)(2, 0, 8)) == il.ILRE_EINVAL
+    assert sel(mk_=(ctypes.c_int32 * 3)(2, 4, 2048)) == il.ILRE_EUNSUPPORTED
+    assert sel(ak_=(ctypes.c_int32 * 2)(1, 4096)) == il.ILRE_EUNSUPPORTED
+    assert sel(n_max=3, n_avg=2, mk_=mk, ak_=ak, L=100000, budget=9000) == il.ILRE_EUNSUPPORTED
+    wide = (ctypes.c_int32 * 9)(*range(1, 10))
+    assert sel(mk_=wide, n_max=9, ak_=wide, n_avg=9) == il.ILRE_EUNSUPPORTED     # 81 combinations
+    # sizing: grows with the number of average kernels, rejects what the entry points reject
+    a = il.ilre_workspace_bytes_max_avg(1 << 20, 256, 32, 8, 128, 4, (2, 4, 8), 16, il.ILRE_BF16)
+    b = il.ilre_workspace_bytes_max_avg(1 << 20, 256, 32, 8, 128, 4, (2, 4, 8), 4, il.ILRE_BF16)
+    assert b < a < (1 << 30)
+    with pytest.raises(il.IlreError):
+        il.ilre_workspace_bytes_max_avg(1000, 8, 8, 2, 128, 4, (0,), 1, il.ILRE_BF16)
+
+    def rope(L=1000, chunk=128, extra=4, base=10000.0, pairing=0, k_in=fake, k_out=fake, opts=o):
+        return lib.ilre_rerope_keys(k_in, k_out, L, 2, 128, chunk, extra, base, None, pairing, ctypes.byref(opts))
+
+    assert rope(k_in=None) == il.ILRE_EINVAL and rope(k_out=None) == il.ILRE_EINVAL
+    assert rope(chunk=0) == il.ILRE_EINVAL and rope(extra=-1) == il.ILRE_EINVAL
+    assert rope(base=0.0) == il.ILRE_EINVAL and rope(pairing=2) == il.ILRE_EUNSUPPORTED
+    assert rope(k_in=ctypes.c_void_p(4100)) == il.ILRE_EINVAL                     # misaligned
+    assert rope(opts=_opts(k_stride_token=100)) == il.ILRE_EINVAL
+    assert lib.ilre_rerope_keys(fake, fake, 1000, 2, 64, 128, 4, 10000.0, None, 0, ctypes.byref(o)) == il.ILRE_EUNSUPPORTED
+
+    assert lib.ilre_gather_ids(None, 1000, fake, 10, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_gather_ids(fake, 1000, fake, -1, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_gather_ids(fake, 1000, fake, 0, fake, ctypes.byref(o)) == il.ILRE_OK   # nothing to do, nothing launched
+    assert il.ilre_last_error()

@@ -353,3 +353,43 @@ def test_extreme_logits_take_the_safe_row_statistics_path(dtype, Lq):
     np.testing.assert_allclose(gm + np.log(gz), want_max + np.log(want_sum), rtol=2e-5, atol=2e-4)
     bad, worst = score_errors(scores.cpu().numpy(), want_score)
     assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
+
+
+def test_recall_replays_from_a_captured_graph():
+    """The library neither allocates nor synchronises, so a whole recall step can be captured into a HIP
+    graph; every replay, with eager work and synchronisations in between, gives the eager result."""
+    _announce("graph capture and replay")
+    inp = inputs.custom(L=30000, Lq=64, Hq=8, Hkv=2, d=128, dtype="bf16", n_spans=4, span_len=(16, 64), seed=12)
+    q, k = to_device(inp.q), to_device(inp.k)
+    kernels, budget, mk, ak = (1, 3, 7, 15, 31), 1024, (2, 4, 8), tuple(range(1, 17))
+    ws = il.alloc_workspace(30000, 64, 8, 2, 128, len(kernels), il.ILRE_BF16)
+    ws2 = il.alloc_workspace_max_avg(30000, 64, 8, 2, 128, 4, mk, len(ak), il.ILRE_BF16)
+    eager_idx, eager_sc = il.ilre_recall(q, k, budget, kernels, workspace=ws)
+    eager_pidx, eager_cnt, _ = il.ilre_recall_max_avg(q, k, budget, mk, ak, 4, workspace=ws2)
+    torch.cuda.synchronize()
+    eager_idx, eager_sc, eager_pidx = eager_idx.clone(), eager_sc.clone(), eager_pidx.clone()
+    out_idx, out_sc = torch.empty_like(eager_idx), torch.empty_like(eager_sc)
+    out_pidx, out_cnt, out_psc = torch.empty_like(eager_pidx), torch.empty_like(eager_cnt), torch.empty_like(eager_sc)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        il.ilre_recall(q, k, budget, kernels, workspace=ws, out_idx=out_idx, out_scores=out_sc)       # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            il.ilre_recall(q, k, budget, kernels, workspace=ws, out_idx=out_idx, out_scores=out_sc)
+            il.ilre_recall_max_avg(q, k, budget, mk, ak, 4, workspace=ws2, out_idx=out_pidx, out_count=out_cnt,
+                                   out_scores=out_psc)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out_idx.fill_(-7)
+        out_sc.zero_()
+        out_pidx.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_idx, eager_idx) and torch.equal(out_sc, eager_sc), f"replay {rep}"
+        assert torch.equal(out_pidx, eager_pidx) and int(out_cnt.item()) == int(eager_cnt.item()), f"replay {rep}"
+        # eager work between the replays
+        again, _ = il.ilre_recall(q, k, budget, kernels, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager_idx)
