@@ -114,13 +114,6 @@ __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t x, uint32_t *w
     return x + before;
 }
 
-__device__ __forceinline__ int pow2_floor(int w)
-{
-    int p = 1;
-    while (2 * p <= w) p *= 2;
-    return p;
-}
-
 __global__ __launch_bounds__(kThreads) void sel_init(const SelParams prm, uint32_t *hist, SelCtrl *ctrl, uint32_t *done)
 {
     const int j = blockIdx.x;
