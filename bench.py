@@ -121,6 +121,15 @@ def main() -> int:
     roofline = {"bound": "mfma", "kernel": dom_name, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4), "traffic": traffic,
                 "flops_per_launch": flops_per_pass, "launch_ms": round(stage_ms[dom], 4)}
+    # Arithmetic intensity of a scoring pass is G*Lq flop per byte of K; below the ridge (peak flops / peak
+    # bytes, about 312 for bf16) the pass is priced against HBM instead: algorithmic bytes = the key cache once.
+    es = 2 if wl.dtype == "bf16" else 4
+    if wl.dtype == "bf16" and (wl.Hq // wl.Hkv) * wl.Lq < PEAK_BF16_TFLOPS * 1e12 / 8e12:
+        k_bytes = float(wl.Hkv) * wl.L * wl.d * es + (4.0 * wl.L if dom == 1 else 0.0)
+        gbs = k_bytes / (stage_ms[dom] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+                    "frac": round(gbs / 8000.0, 4), "traffic": traffic, "bytes_per_launch": k_bytes,
+                    "launch_ms": round(stage_ms[dom], 4)}
 
     result = {
         "metric": "context tokens/sec recalled at L=1M (single GPU)" if args.config == 5
@@ -136,6 +145,9 @@ def main() -> int:
         "stage_tflops": {"row_stats": round(flops_per_pass / stage_ms[0] / 1e9, 1),
                          "col_scores": round(flops_per_pass / stage_ms[1] / 1e9, 1)},
         "roofline": roofline,
+        # the definition computes Q K^T once; the second pass is a recompute forced by memory
+        "useful": {"flops_counted_once": flops_per_pass, "tflops": round(flops_per_pass / (ms_per_step * 1e-3) / 1e12, 1),
+                   "frac_of_peak": round(flops_per_pass / (ms_per_step * 1e-3) / 1e12 / peak, 4)},
     }
 
     if not args.no_paper_allocation:
