@@ -393,3 +393,38 @@ def test_recall_replays_from_a_captured_graph():
         again, _ = il.ilre_recall(q, k, budget, kernels, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(again, eager_idx)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_randomised_against_oracle(seed):
+    """Many small random problems per seed, both forms of Algorithm 1: sizes around the chunk, bin and list
+    boundaries of the kernels, score distributions with and without ties, all bit-exact with the oracle."""
+    _announce(f"randomised selection, seed {seed}")
+    rng = np.random.default_rng(9000 + seed)
+    kinds = ("random", "few_values", "two_values", "equal", "narrow", "needles")
+    for case in range(40):
+        L = int(rng.choice([1, 2, 63, 64, 65, 255, 256, 257, 511, 513, 1000, 2047, 2049, 4097, 9999, 20000]))
+        L = max(1, L + int(rng.integers(-3, 4)))
+        kind = kinds[int(rng.integers(len(kinds)))]
+        s = _scores_for(kind, L, rng) if L > 400 or kind != "needles" else rng.random(L).astype(np.float32)
+        budget = int(rng.choice([1, 2, 7, 64, 255, 1000, 4096, 8192]))
+        if min(budget, L) > 8192:
+            budget = 8192
+        dev = torch.from_numpy(s).cuda()
+        if case % 2 == 0:
+            n = int(rng.integers(1, 7))
+            kernels = tuple(int(2 * rng.integers(0, 40) + 1) for _ in range(n))
+            want = oracle.allocate(s, kernels, budget)
+            got = il.ilre_select(dev, budget, kernels)
+            torch.cuda.synchronize()
+            assert got.cpu().numpy().tolist() == want.tolist(), (seed, case, L, kind, budget, kernels)
+        else:
+            mk = tuple(int(rng.integers(1, 20)) for _ in range(int(rng.integers(1, 4))))
+            ak = tuple(int(rng.integers(1, 24)) for _ in range(int(rng.integers(1, 5))))
+            sink = int(rng.integers(0, min(L, 6) + 1))
+            want = oracle.allocate_max_avg(s, mk, ak, budget, sink=sink)
+            got, count = il.ilre_select_max_avg(dev, budget, mk, ak, sink)
+            torch.cuda.synchronize()
+            n_got = int(count.item())
+            got = got.cpu().numpy()
+            assert got[:n_got].tolist() == want.tolist() and (got[n_got:] == -1).all(), (seed, case, L, kind, budget, mk, ak, sink)
