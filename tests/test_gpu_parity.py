@@ -71,6 +71,29 @@ def test_staged_scoring(name, L, Lq, Hq, Hkv, dtype, cs):
     assert bad == 0, f"max mode: {bad} scores out of tolerance, worst {worst:.2f}x"
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_scoring_randomised_shapes(seed):
+    """Random shapes around the kernels' block sizes (32-row query blocks, 64/128-token tiles, 4- and 8-wave
+    workgroups, several token splits), both element types, sum and max reduction, whole path."""
+    _announce(f"randomised scoring shapes, seed {seed}")
+    rng = np.random.default_rng(7000 + seed)
+    for case in range(6):
+        Hkv = int(rng.choice([1, 2, 3]))
+        G = int(rng.choice([1, 2, 4, 5]))
+        Lq = int(rng.choice([1, 7, 31, 33, 64, 100, 130]))
+        L = int(rng.choice([1, 31, 64, 127, 129, 1000, 4097, 12000])) + int(rng.integers(0, 3))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        inp = inputs.custom(L=L, Lq=Lq, Hq=Hkv * G, Hkv=Hkv, d=128, dtype=dtype, n_spans=1 if L > 300 else 0,
+                            span_len=(8, 24), channel_scale=bool(rng.integers(2)), seed=100 * seed + case)
+        q, k = to_device(inp.q), to_device(inp.k)
+        mode = oracle.MODE_MAX if case % 3 == 2 else oracle.MODE_SUM
+        want, _, _ = oracle.scores(inp.q, inp.k, mode=mode)
+        _, got = il.ilre_recall(q, k, 16, (3,), score_mode=il.ILRE_SCORE_MAX if mode == oracle.MODE_MAX else il.ILRE_SCORE_SUM)
+        torch.cuda.synchronize()
+        bad, worst = score_errors(got.cpu().numpy(), want)
+        assert bad == 0, (seed, case, L, Lq, Hkv, G, dtype, mode, bad, worst)
+
+
 SELECT_CASES = [
     # name, L, kernels, budget, kind
     ("random_small", 3000, (3, 7, 15), 256, "random"),
