@@ -278,15 +278,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 
     // Pass 2: combine the NPART partial column results of a finished tile in a fixed order.  Wave w
     // takes tokens 16w..16w+15, four lanes per token, each lane NPART/4 partials, then the quad.
-    auto flush_columns = [&](int64_t tile) {
-        const float *rb = red + (int)((tile - tile0) % 3) * NPART * RSTR;
+    // In the tile loop the LDS reads are issued at the top of a tile and consumed one unit later, so
+    // that their latency hides behind that unit's MFMAs.
+    float fl[NPART / 4];
+    auto flush_load = [&](int64_t tile) {
+        const float *rb = red + (int)(tile - tile0) % 3 * NPART * RSTR;
         const int tl = wave * 16 + (lane >> 2), part0 = (lane & 3) * (NPART / 4);
-        float acc = rb[part0 * RSTR + tl];
 #pragma unroll
-        for (int k = 1; k < NPART / 4; ++k) {
-            const float x = rb[(part0 + k) * RSTR + tl];
-            acc = RMAX ? fmaxf(acc, x) : acc + x;
-        }
+        for (int k = 0; k < NPART / 4; ++k) fl[k] = rb[(part0 + k) * RSTR + tl];
+    };
+    auto flush_finish = [&](int64_t tile) {
+        const int tl = wave * 16 + (lane >> 2);
+        float acc = fl[0];
+#pragma unroll
+        for (int k = 1; k < NPART / 4; ++k) acc = RMAX ? fmaxf(acc, fl[k]) : acc + fl[k];
         const float x1 = quad_swap1(acc);
         acc = RMAX ? fmaxf(acc, x1) : acc + x1;
         const float x2 = quad_swap2(acc);
@@ -294,12 +299,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         const int64_t tok = tile * TN + tl;
         if ((lane & 3) == 0 && tok < a.L) a.partial[(int64_t)unit * a.L + tok] = acc;
     };
+    auto flush_columns = [&](int64_t tile) {
+        flush_load(tile);
+        flush_finish(tile);
+    };
 
     // The softmax arithmetic of one finished 32x32 block ("unit": token block tb, query block b).
     // It runs one unit behind the MFMAs, so that the matrix pipe works on unit u while the vector
     // pipe exponentiates unit u-1 from the other accumulator.
     float col = 0.f;  // pass 2: running column result of the token block over its NB query blocks
-    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, auto masked_tag, auto frozen_tag, bool store) {
+    // `rb` is the partial-result buffer (0..2) of the unit's tile, pass 2 only.
+    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, int rb, auto masked_tag, auto frozen_tag, bool store) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr bool FROZEN = decltype(frozen_tag)::value;
         if (MODE == 0) {
@@ -326,7 +336,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
             else
                 col = RMAX ? fmaxf(col, part) : col + part;
             if (b == NB - 1 && store)
-                red[((int)((tile - tile0) % 3) * NPART + wave * 2 + half) * RSTR + tb * 32 + l32] = col;
+                red[(rb * NPART + wave * 2 + half) * RSTR + tb * 32 + l32] = col;
         }
     };
 
@@ -358,8 +368,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         constexpr bool CUR_RAGGED = decltype(ragged_tag)::value;
         constexpr bool FROZEN = decltype(frozen_tag)::value;  // pass 1: reference maxima no longer move
         const int it = (int)(tile - tile0);
+        const int rb_cur = it % 3, rb_prev = (it + 2) % 3;
         if (tile + 2 < tile1) issue_tile(tile + 2, (it + 2) % 3);
-        if (MODE == 1 && it >= 2) flush_columns(tile - 2);
+        if (MODE == 1 && it >= 2) flush_load(tile - 2);
         // byte distance from this tile's buffer to the next tile's
         const int to_next = (it % 3 == 2) ? -2 * TILE_BYTES : TILE_BYTES;
 
@@ -386,12 +397,13 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
                 }
                 kf[st] = *(const uint4 *)((__attribute__((address_space(3))) unsigned char *)(size_t)frag_addr[st] + next_block);
             }
+            if (MODE == 1 && u == 1 && it >= 2) flush_finish(tile - 2);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 if (u == 0)
-                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, std::false_type{}, frozen_tag, it > 0);
+                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, rb_prev, std::false_type{}, frozen_tag, it > 0);
                 else
-                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, std::bool_constant<CUR_RAGGED>{}, frozen_tag, true);
+                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, rb_cur, std::bool_constant<CUR_RAGGED>{}, frozen_tag, true);
             }
             // ask the scheduler for: one MFMA (group), a slice of the vector work, and a fragment
             // read after every NB-th MFMA
@@ -424,12 +436,13 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         for (; tile < tile_full_end; ++tile) do_tile(tile, std::false_type{}, std::true_type{});
     if (last_ragged) do_tile(tile1 - 1, std::true_type{}, std::false_type{});
     // drain the pipeline: the last unit of the last tile
+    const int rb_last = (int)((tile1 - 1 - tile0) % 3);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (last_ragged)
-            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::true_type{}, std::false_type{}, true);
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::true_type{}, std::false_type{}, true);
         else
-            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, std::false_type{}, std::false_type{}, true);
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::false_type{}, std::false_type{}, true);
     }
 
     if (MODE == 1) {
