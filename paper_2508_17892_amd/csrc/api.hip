@@ -275,6 +275,7 @@ int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, i
     a.row_max = row_max;
     a.row_sumexp = row_sumexp;
     a.partial = (float *)(ws + lay.partial);
+    a.dump = (float *)(ws + lay.flag) + 16;
     const hipError_t e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "column-score launch");
     return ILRE_OK;
@@ -338,6 +339,7 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     a.row_max = row_max;
     a.row_sumexp = row_sumexp;
     a.partial = (float *)(ws + lay.partial);
+    a.dump = (float *)(ws + lay.flag) + 16;
     e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s);
     if (e != hipSuccess) return hip_fail(e, "column-score launch");
     return ILRE_OK;

@@ -49,6 +49,7 @@ struct ScoreArgs {
     // pass 2 (column scores)
     const float *row_max, *row_sumexp;  // [Hq*Lq]
     float *partial;                     // [nunits][L]
+    float *dump;                        // 16 floats nobody reads: target of stores that have nothing to store
 };
 
 ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv);

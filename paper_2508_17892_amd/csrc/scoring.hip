@@ -278,8 +278,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 
     // Pass 2: combine the NPART partial column results of a finished tile in a fixed order.  Wave w
     // takes tokens 16w..16w+15, four lanes per token, each lane NPART/4 partials, then the quad.
-    // In the tile loop the LDS reads are issued at the top of a tile and consumed one unit later, so
-    // that their latency hides behind that unit's MFMAs.
+    // In the tile loop the LDS reads are issued inside the first unit and consumed in the last one, so
+    // that their latency hides behind MFMAs.
     float fl[NPART / 4];
     auto flush_load = [&](int64_t tile) {
         const float *rb = red + (int)(tile - tile0) % 3 * NPART * RSTR;
@@ -287,7 +287,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 #pragma unroll
         for (int k = 0; k < NPART / 4; ++k) fl[k] = rb[(part0 + k) * RSTR + tl];
     };
-    auto flush_finish = [&](int64_t tile) {
+    // `live` false: nothing to flush yet.  Lanes with nothing to store write to a dump slot instead of
+    // branching around the store, which would cut the tile body into separately scheduled pieces.
+    auto flush_finish = [&](int64_t tile, bool live) {
         const int tl = wave * 16 + (lane >> 2);
         float acc = fl[0];
 #pragma unroll
@@ -297,11 +299,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         const float x2 = quad_swap2(acc);
         acc = RMAX ? fmaxf(acc, x2) : acc + x2;
         const int64_t tok = tile * TN + tl;
-        if ((lane & 3) == 0 && tok < a.L) a.partial[(int64_t)unit * a.L + tok] = acc;
+        float *dst = (live && (lane & 3) == 0 && tok < a.L) ? a.partial + ((int64_t)unit * a.L + tok) : a.dump + (lane & 15);
+        *dst = acc;
     };
     auto flush_columns = [&](int64_t tile) {
         flush_load(tile);
-        flush_finish(tile);
+        flush_finish(tile, true);
     };
 
     // The softmax arithmetic of one finished 32x32 block ("unit": token block tb, query block b).
@@ -309,7 +312,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // pipe exponentiates unit u-1 from the other accumulator.
     float col = 0.f;  // pass 2: running column result of the token block over its NB query blocks
     // `rb` is the partial-result buffer (0..2) of the unit's tile, pass 2 only.
-    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, int rb, auto masked_tag, auto frozen_tag, bool store) {
+    auto finish_unit = [&](const f32x16 &acc, int b, int tb, int64_t tile, int rb, auto masked_tag, auto frozen_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr bool FROZEN = decltype(frozen_tag)::value;
         if (MODE == 0) {
@@ -335,8 +338,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
                 col = part;
             else
                 col = RMAX ? fmaxf(col, part) : col + part;
-            if (b == NB - 1 && store)
-                red[(rb * NPART + wave * 2 + half) * RSTR + tb * 32 + l32] = col;
+            // (the unit before a split's very first one stores zeros into a buffer that is rewritten
+            // before it is read: no condition here, the tile body stays free of branches)
+            if (b == NB - 1) red[(rb * NPART + wave * 2 + half) * RSTR + tb * 32 + l32] = col;
         }
     };
 
@@ -370,7 +374,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         const int it = (int)(tile - tile0);
         const int rb_cur = it % 3, rb_prev = (it + 2) % 3;
         if (tile + 2 < tile1) issue_tile(tile + 2, (it + 2) % 3);
-        if (MODE == 1 && it >= 2) flush_load(tile - 2);
         // byte distance from this tile's buffer to the next tile's
         const int to_next = (it % 3 == 2) ? -2 * TILE_BYTES : TILE_BYTES;
 
@@ -397,13 +400,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
                 }
                 kf[st] = *(const uint4 *)((__attribute__((address_space(3))) unsigned char *)(size_t)frag_addr[st] + next_block);
             }
-            if (MODE == 1 && u == 1 && it >= 2) flush_finish(tile - 2);
+            // column results of the tile before the previous one: LDS reads behind the first unit's
+            // MFMAs (in straight-line code, so the fragment waits can leave them in flight), sums and
+            // store in the tile's last unit
+            if (MODE == 1 && u == 0) flush_load(it >= 2 ? tile - 2 : tile);
+            if (MODE == 1 && u == UNITS - 1) flush_finish(tile - 2, it >= 2);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 if (u == 0)
-                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, rb_prev, std::false_type{}, frozen_tag, it > 0);
+                    finish_unit(acc[1][b], b, UNITS - 1, tile - 1, rb_prev, std::false_type{}, frozen_tag);
                 else
-                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, rb_cur, std::bool_constant<CUR_RAGGED>{}, frozen_tag, true);
+                    finish_unit(acc[(u - 1) & 1][b], b, u - 1, tile, rb_cur, std::bool_constant<CUR_RAGGED>{}, frozen_tag);
             }
             // ask the scheduler for: one MFMA (group), a slice of the vector work, and a fragment
             // read after every NB-th MFMA
@@ -440,9 +447,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (last_ragged)
-            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::true_type{}, std::false_type{}, true);
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::true_type{}, std::false_type{});
         else
-            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::false_type{}, std::false_type{}, true);
+            finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::false_type{}, std::false_type{});
     }
 
     if (MODE == 1) {
