@@ -73,8 +73,11 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // Online update of one query row's running (max, sum of exponentials) with 16 new logits.
 // Logits are raw dot products; c = scale*log2(e) turns them into base-2 exponents.
+// A row's running sum is kept as four partial sums (accumulator registers v, v+4, v+8, v+12 feed
+// partial v & 3), so that an element costs exactly one fma, one exp2 and one add; they are added up
+// once, when the kernel ends.
 template <bool MASKED>
-__device__ __forceinline__ void row_update(const f32x16 &acc, float c, float &m, float &z, int64_t tok0, int64_t L)
+__device__ __forceinline__ void row_update(const f32x16 &acc, float c, float &m, float (&z)[4], int64_t tok0, int64_t L)
 {
     float s[16];
 #pragma unroll
@@ -89,18 +92,13 @@ __device__ __forceinline__ void row_update(const f32x16 &acc, float c, float &m,
 #pragma unroll
     for (int v = 1; v < 16; ++v) smax = fmaxf(smax, s[v]);
     const float mnew = fmaxf(m, smax * c);
-    z *= fast_exp2(m - mnew);
+    const float rescale = fast_exp2(m - mnew);
     m = mnew;
     const float nm = -mnew;
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; v += 4) {
-        p0 += fast_exp2(fmaf(s[v + 0], c, nm));
-        p1 += fast_exp2(fmaf(s[v + 1], c, nm));
-        p2 += fast_exp2(fmaf(s[v + 2], c, nm));
-        p3 += fast_exp2(fmaf(s[v + 3], c, nm));
-    }
-    z += (p0 + p1) + (p2 + p3);
+    for (int k = 0; k < 4; ++k) z[k] *= rescale;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) z[v & 3] += fast_exp2(fmaf(s[v], c, nm));
 }
 
 // Asynchronous 16-byte-per-lane copy from a buffer resource straight into LDS: lane l of the
@@ -126,18 +124,11 @@ __device__ __forceinline__ float quad_swap2(float x)  // lanes 0<->2, 1<->3 of e
 // The same sum against a frozen reference m: no maximum, no rescale.  Any finite m gives the same
 // (m, z) pair up to rounding as long as 2^(x - m) stays in range; a row whose later logits exceed m by
 // more than ~2^7 base-2 units overflows to inf, which the caller detects and redoes with row_update.
-__device__ __forceinline__ void row_accumulate(const f32x16 &acc, float c, float m, float &z)
+__device__ __forceinline__ void row_accumulate(const f32x16 &acc, float c, float m, float (&z)[4])
 {
     const float nm = -m;
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; v += 4) {
-        p0 += fast_exp2(fmaf(acc[v + 0], c, nm));
-        p1 += fast_exp2(fmaf(acc[v + 1], c, nm));
-        p2 += fast_exp2(fmaf(acc[v + 2], c, nm));
-        p3 += fast_exp2(fmaf(acc[v + 3], c, nm));
-    }
-    z += (p0 + p1) + (p2 + p3);
+    for (int v = 0; v < 16; ++v) z[v & 3] += fast_exp2(fmaf(acc[v], c, nm));
 }
 
 // MODE 0: row statistics.  MODE 1: column scores (RMAX = 0 sum over rows, 1 max over rows).
@@ -248,7 +239,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     for (int st = 0; st < STEPS; ++st) frag_addr[st] = lds0 + l32 * ROWB + (((2 * st + half) ^ (l32 & 15)) * 16);
 
     // pass-1 state: one (max, sum) per owned query row, in base-2 exponent units
-    float m[NB], z[NB];
+    float m[NB], z[NB][4];
     // pass-2 state: per accumulator register the row's exponent offset -(max*log2e + log2 sum)
     float noff[MODE == 1 ? NB : 1][16];
     float *red = (float *)(smem + 3 * TILE_BYTES);  // [3][NPART][RSTR], pass 2 only
@@ -258,7 +249,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             m[b] = kNegBig;
-            z[b] = 0.f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) z[b][k] = 0.f;
         }
     } else {
 #pragma unroll
@@ -461,10 +453,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         // (max, sum) per row and split.
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
+            const float zb = (z[b][0] + z[b][1]) + (z[b][2] + z[b][3]);
             const float mo = __shfl_xor(m[b], 32);
-            const float zo = __shfl_xor(z[b], 32);
+            const float zo = __shfl_xor(zb, 32);
             const float mm = fmaxf(m[b], mo);
-            const float zz = z[b] * fast_exp2(m[b] - mm) + zo * fast_exp2(mo - mm);
+            const float zz = zb * fast_exp2(m[b] - mm) + zo * fast_exp2(mo - mm);
             const int rl = rl0 + b * 32 + l32;
             if (half == 0 && rl < a.rows_per_group) {
                 const int64_t r = (int64_t)(g * a.G + rl / a.Lq) * a.Lq + rl % a.Lq;
