@@ -89,6 +89,11 @@ __device__ __forceinline__ uint32_t load_u32(const uint32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ uint64_t load_u64(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Inclusive prefix sum over the THREADS threads of the block; wsum is THREADS / 64 words of LDS
 // scratch.  Every thread also receives the block total.  Contains two barriers.
 template <int THREADS>
@@ -488,7 +493,7 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
         if (threadIdx.x < 256) h[threadIdx.x] = 0;
         if (threadIdx.x < 2) cnt[threadIdx.x] = 0;
         __syncthreads();
-        for (uint32_t i = threadIdx.x; i < nA; i += kThreads) atomicAdd(&h[(A[i] >> shift) & 255u], 1u);
+        for (uint32_t i = threadIdx.x; i < nA; i += kThreads) atomicAdd(&h[(load_u64(&A[i]) >> shift) & 255u], 1u);
         __syncthreads();
         if (threadIdx.x < 64) {
             // lane l owns digits 255-4l .. 252-4l (descending); find the digit holding the need-th key
@@ -523,12 +528,15 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
         for (uint32_t it = 0; it < rounds; ++it) {
             const uint32_t i = it * kThreads + threadIdx.x;
             const bool valid = i < nA;
-            const uint64_t key = valid ? A[i] : 0;
+            const uint64_t key = valid ? load_u64(&A[i]) : 0;
             const uint32_t d = (uint32_t)(key >> shift) & 255u;
             wave_append(valid && d > digit, key, cand_j + candn, &cnt[0]);
             wave_append(valid && d == digit, key, B, &cnt[1]);
         }
-        __threadfence();
+        // The survivors go through global memory to the next pass of this same workgroup: wait until
+        // the stores have reached the L2 and read them back past the L1 (load_u64).  A fence would do
+        // too, at the price of an L2 write-back per pass.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         candn += above;
         need -= above;
@@ -537,7 +545,7 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
         A = B;
         B = t;
     }
-    for (uint32_t i = threadIdx.x; i < nA; i += kThreads) cand_j[candn + i] = A[i];
+    for (uint32_t i = threadIdx.x; i < nA; i += kThreads) cand_j[candn + i] = load_u64(&A[i]);
     const uint32_t total = candn + nA;
     if (threadIdx.x == 0) ctrl[j].total_n = total;
     if (!ctrl[j].exact) return;  // uniform
@@ -549,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this workgroup's stores to cand_j have reached the L2
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < sort_n; i += kThreads)
-        srt[i] = i < total ? __hip_atomic_load(&cand_j[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+        srt[i] = i < total ? load_u64(&cand_j[i]) : 0ull;
     __syncthreads();
     for (uint32_t k = 2; k <= sort_n; k <<= 1) {
         for (uint32_t d = k >> 1; d > 0; d >>= 1) {
@@ -1099,7 +1107,12 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
                 cp.off[i] = cell_off;
                 cell_off += (uint64_t)len;
             }
-            const int64_t km = (int64_t)budget / cell + 1;
+            // K_m = B / m + 1 cells are candidates; of those the walk can only reach the first
+            // ceil((shares up to and including this one) / m): at most (shares before) tokens are taken
+            // when it starts and it stops after B_c free ones.  Only that many are found and sorted.
+            int64_t km = (int64_t)budget / cell + 1;
+            const int64_t reach = (before + share + cell - 1) / cell;
+            if (reach < km) km = reach;
             prm.want[j] = (uint32_t)(km < len ? km : len);
             prm.before[j] = (uint32_t)((na - 1) / 2);
             prm.after[j] = (uint32_t)(na / 2);
