@@ -350,12 +350,27 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const int64_t el = fc * kSelFine + lane + k * 64;
-            if (el >= pl.len) continue;
             const uint32_t key = ordered_bits(pooled[k]);
-            if (LEVEL == 1)
-                atomicAdd(&lh[key >> 21], 1u);
-            else if ((key >> 21) == bin1)
+            if (LEVEL == 1) {
+                // Real score distributions put most of a wavefront's 64 keys into one or two bins, and
+                // same-address LDS atomics serialise: the two most common bins are counted with ballots
+                // and added once, whatever is left goes one by one.
+                const uint32_t bin = key >> 21;
+                bool todo = el < pl.len;
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const uint64_t open = __ballot(todo);
+                    if (open == 0) break;  // uniform
+                    const int leader = __ffsll((unsigned long long)open) - 1;
+                    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+                    const uint64_t same = __ballot(todo && bin == b0);
+                    if (lane == leader) atomicAdd(&lh[b0], (uint32_t)__popcll(same));
+                    todo = todo && bin != b0;
+                }
+                if (todo) atomicAdd(&lh[bin], 1u);
+            } else if (el < pl.len && (key >> 21) == bin1) {
                 atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
+            }
         }
     }
     __syncthreads();
