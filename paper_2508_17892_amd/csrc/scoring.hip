@@ -291,7 +291,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         const float x2 = quad_swap2(acc);
         acc = RMAX ? fmaxf(acc, x2) : acc + x2;
         const int64_t tok = tile * TN + tl;
-        float *dst = (live && (lane & 3) == 0 && tok < a.L) ? a.partial + ((int64_t)unit * a.L + tok) : a.dump + (lane & 15);
+        // after the quad reduction the four lanes of a token hold the same value and all store it
+        float *dst = (live && tok < a.L) ? a.partial + ((int64_t)unit * a.L + tok) : a.dump + (lane & 15);
         *dst = acc;
     };
     auto flush_columns = [&](int64_t tile) {
