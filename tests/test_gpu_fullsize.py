@@ -95,3 +95,91 @@ def test_fullsize_printed_allocation_against_oracle_digest(cfg, golden_dir):
     unexcused = sorted(diff - set(ma["excused_tokens"]))
     assert not unexcused, f"{len(unexcused)} unexcused index differences, e.g. {unexcused[:8]}"
     print(f"[case] fullsize printed allocation cfg{cfg}: kept {n}, index sym diff {len(diff)} (all excused)", flush=True)
+
+
+def test_select_at_the_largest_context_the_abi_allows():
+    """L = 2^31 - 1 scores (8 GiB): every index computation at its limit, pruning pre-pass active.  The scores
+    are a constant background with isolated peaks, so the expected result comes from the oracle run on the
+    peaks' neighbourhoods alone: pooled values there are what they are in the full vector, ranks keep their
+    order, and the background is never reached."""
+    import oracle
+    L, budget, kernels = (1 << 31) - 1, 4096, (1, 7, 31)
+    print(f"[case] select L={L} kernels={kernels} budget={budget}", flush=True)
+    rng = np.random.default_rng(31)
+    n_peaks, gap = 3000, 64
+    slots = np.sort(rng.choice(L // gap - 2, size=n_peaks, replace=False)) + 1
+    pos = slots * gap + rng.integers(0, 8, size=n_peaks)          # isolated: at least 56 apart
+    pos[0], pos[-1] = 3, L - 2                                     # two of them at the very ends of the context
+    vals = (1.0 + rng.random(n_peaks)).astype(np.float32)
+    background = np.float32(0.25)
+    # oracle on the neighbourhoods: 20 tokens either side of every peak, one background token between them
+    R = 20
+    pieces, origin = [], []
+    for p, v in zip(pos.tolist(), vals.tolist()):
+        lo, hi = max(0, p - R), min(L, p + R + 1)
+        seg = np.full(hi - lo, background, dtype=np.float32)
+        seg[p - lo] = v
+        pieces.append(seg)
+        origin.append(np.arange(lo, hi, dtype=np.int64))
+    small = np.concatenate(pieces)
+    origin = np.concatenate(origin)
+    assert (np.diff(origin) > 0).all()
+    picked = oracle.allocate(small, kernels, budget)
+    pooled_any = np.zeros(small.size, dtype=bool)
+    for w in kernels:
+        pooled_any |= oracle.max_pool_same(small, w) > background
+    assert pooled_any[picked].all(), "the budget must be met without touching the background"
+    want = origin[picked]
+
+    scores = torch.full((L,), float(background), dtype=torch.float32, device="cuda")
+    scores[torch.from_numpy(pos).cuda()] = torch.from_numpy(vals).cuda()
+    ws = il.alloc_workspace(L, 1, 1, 1, 128, len(kernels), il.ILRE_F32)
+    got = il.ilre_select(scores, budget, kernels, workspace=ws)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    check_index_structure(got, L, budget)
+    assert got.tolist() == want.tolist()
+    assert got[0] <= 3 and got[-1] >= L - 3
+
+
+def test_select_max_avg_at_the_largest_context_the_abi_allows():
+    """The printed form at L = 2^31 - 1 (max kernel 8, average kernels 1 and 2, sink 5): expected values from
+    the oracle on the peaks' cell-aligned neighbourhoods, which carry the same cell averages as the full
+    vector; every candidate must lie above the background for that to hold, and does."""
+    import oracle
+    L, sink, budget, mk, ak = (1 << 31) - 1, 5, 4096, (8,), (1, 2)
+    print(f"[case] select_max_avg L={L} max={mk} avg={ak} sink={sink} budget={budget}", flush=True)
+    Lb = L - sink
+    cells = Lb // 8
+    rng = np.random.default_rng(32)
+    n_peaks, gap = 2500, 32                                         # in cells
+    pc = np.sort(rng.choice(cells // gap - 2, size=n_peaks, replace=False)) + 1
+    pc = pc * gap + rng.integers(0, 4, size=n_peaks)                 # peak cells, isolated
+    pc[0], pc[-1] = 0, cells - 1                                     # first and last whole cell
+    pos = pc * 8 + rng.integers(0, 8, size=n_peaks)                  # body coordinates
+    vals = (1.0 + rng.random(n_peaks)).astype(np.float32)
+    background = np.float32(0.25)
+    R = 6                                                            # cells either side
+    pieces, origin = [], []
+    for c, p, v in zip(pc.tolist(), pos.tolist(), vals.tolist()):
+        lo, hi = max(0, c - R) * 8, min(cells, c + R + 1) * 8
+        seg = np.full(hi - lo, background, dtype=np.float32)
+        seg[p - lo] = v
+        pieces.append(seg)
+        origin.append(np.arange(lo, hi, dtype=np.int64))
+    small = np.concatenate(pieces)
+    origin = np.concatenate(origin)
+    assert (np.diff(origin) > 0).all() and origin[0] == 0 and origin[-1] == cells * 8 - 1
+    picked = oracle.allocate_max_avg(small, mk, ak, budget, sink=0)
+    for _, last, cap in oracle.thresholds_max_avg(small, mk, ak, budget, sink=0):
+        assert cap is not None and cap > background and last > background
+    want = np.concatenate([np.arange(sink), origin[picked] + sink])
+
+    scores = torch.full((L,), float(background), dtype=torch.float32, device="cuda")
+    scores[:sink] = 9.0                                              # sink scores are never looked at
+    scores[torch.from_numpy(pos + sink).cuda()] = torch.from_numpy(vals).cuda()
+    got, count = il.ilre_select_max_avg(scores, budget, mk, ak, sink)
+    torch.cuda.synchronize()
+    n = int(count.item())
+    got = got.cpu().numpy()
+    assert n == want.size and got[:n].tolist() == want.tolist() and (got[n:] == -1).all()
