@@ -183,3 +183,25 @@ def test_select_max_avg_at_the_largest_context_the_abi_allows():
     n = int(count.item())
     got = got.cpu().numpy()
     assert n == want.size and got[:n].tolist() == want.tolist() and (got[n:] == -1).all()
+
+
+def test_scoring_across_the_4gib_offset_of_a_token_major_cache():
+    """2.2M tokens x 8 kv heads in token-major storage: byte offsets inside the cache pass 4 GiB.  Few query
+    rows, so the oracle computes every score."""
+    import oracle
+    L, Lq, H = 2_200_000, 2, 8
+    print(f"[case] scoring token-major L={L} Hkv={H}", flush=True)
+    inp = inputs.custom(L=L, Lq=Lq, Hq=H, Hkv=H, d=128, dtype="bf16", n_spans=8, span_len=(64, 64), seed=44)
+    want, _, _ = oracle.scores(inp.q, inp.k)
+    q = to_device(inp.q)
+    k_tm = to_device(np.ascontiguousarray(inp.k.transpose(1, 0, 2))).permute(1, 0, 2)      # storage [L, Hkv, d]
+    assert k_tm.stride(1) * k_tm.element_size() * (L - 1) > (1 << 32)
+    idx, scores = il.ilre_recall(q, k_tm, 1024, (3, 7))
+    torch.cuda.synchronize()
+    bad, worst = score_errors(scores.cpu().numpy(), want)
+    assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
+    rep_idx = idx.cpu().numpy()
+    check_index_structure(rep_idx, L, 1024)
+    from parity import index_set_report
+    rep = index_set_report(rep_idx, want, (3, 7), 1024)
+    assert not rep["unexcused"], rep
