@@ -205,3 +205,23 @@ def test_scoring_across_the_4gib_offset_of_a_token_major_cache():
     from parity import index_set_report
     rep = index_set_report(rep_idx, want, (3, 7), 1024)
     assert not rep["unexcused"], rep
+
+    # the re-RoPE pass on the same cache, in place, checked on sampled tokens either side of the 4 GiB offset
+    chunk, extra, base = 1024, 4, 500000.0
+    rng = np.random.default_rng(45)
+    toks = np.unique(np.concatenate([rng.integers(0, L, size=1500), np.arange(L - 3000, L, 7), np.arange(0, 3000, 7),
+                                     np.arange(2_097_000, 2_098_000, 3)]))
+    bounds = oracle.chunk_bounds(L, chunk, extra)
+    dist = np.array(oracle.chunk_distances(len(bounds), chunk))
+    ci = np.where(toks < extra + chunk, 0, (toks - extra) // chunk)
+    freq = oracle.default_inv_freq(128, base)
+    src = inputs.as_float(inp.k[:, toks, :]).astype(np.float64)
+    exact = np.stack([oracle.rotate(src[:, i, :], dist[ci[i]], freq) for i in range(toks.size)], axis=1)
+    il.ilre_rerope_keys(k_tm, chunk, extra, rope_base=base, out=k_tm)
+    torch.cuda.synchronize()
+    got_bits = k_tm[:, torch.from_numpy(toks).cuda(), :].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    got = inputs.bf16_bits_to_f32(got_bits).astype(np.float64)
+    tol = np.abs(exact) * 2.0 ** -8 * 1.001 + 2e-6 * np.abs(src).max(axis=-1, keepdims=True)
+    assert (np.abs(got - exact) <= tol).all()
+    assert (inputs.f32_to_bf16_bits(exact.astype(np.float32)) != got_bits).mean() < 2e-3
+    assert dist[ci].max() > 2_000_000 and (dist[ci] == 0).any()
