@@ -94,17 +94,52 @@ __device__ __forceinline__ uint64_t load_u64(const uint64_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Wavefront scans and reductions with DPP row shifts and row broadcasts: six plain vector instructions,
+// where a shuffle-based version pays six trips through the LDS crossbar.
+#define ILRE_DPP(old, x, ctrl, rows) __builtin_amdgcn_update_dpp((int)(old), (int)(x), ctrl, rows, 0xF, false)
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t x)  // inclusive prefix sum over the 64 lanes
+{
+    x += (uint32_t)ILRE_DPP(0, x, 0x111, 0xF);  // row_shr:1
+    x += (uint32_t)ILRE_DPP(0, x, 0x112, 0xF);  // row_shr:2
+    x += (uint32_t)ILRE_DPP(0, x, 0x114, 0xF);  // row_shr:4
+    x += (uint32_t)ILRE_DPP(0, x, 0x118, 0xF);  // row_shr:8
+    x += (uint32_t)ILRE_DPP(0, x, 0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+    x += (uint32_t)ILRE_DPP(0, x, 0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_total(uint32_t scanned)  // lane 63 of an inclusive scan, in every lane
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)scanned, 63);
+}
+template <bool IS_AND>
+__device__ __forceinline__ uint32_t wave_bits32(uint32_t x)  // AND or OR over the 64 lanes, in every lane
+{
+    const uint32_t id = IS_AND ? 0xFFFFFFFFu : 0u;
+#define ILRE_STEP(ctrl, rows)                                      \
+    {                                                              \
+        const uint32_t y = (uint32_t)ILRE_DPP(id, x, ctrl, rows);  \
+        x = IS_AND ? (x & y) : (x | y);                            \
+    }
+    ILRE_STEP(0x111, 0xF) ILRE_STEP(0x112, 0xF) ILRE_STEP(0x114, 0xF) ILRE_STEP(0x118, 0xF) ILRE_STEP(0x142, 0xA) ILRE_STEP(0x143, 0xC)
+#undef ILRE_STEP
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ uint64_t wave_and64(uint64_t x)
+{
+    return ((uint64_t)wave_bits32<true>((uint32_t)(x >> 32)) << 32) | wave_bits32<true>((uint32_t)x);
+}
+__device__ __forceinline__ uint64_t wave_or64(uint64_t x)
+{
+    return ((uint64_t)wave_bits32<false>((uint32_t)(x >> 32)) << 32) | wave_bits32<false>((uint32_t)x);
+}
+
 // Inclusive prefix sum over the THREADS threads of the block; wsum is THREADS / 64 words of LDS
 // scratch.  Every thread also receives the block total.  Contains two barriers.
 template <int THREADS>
 __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t x, uint32_t *wsum, uint32_t &total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t y = __shfl_up(x, d);
-        if (lane >= d) x += y;
-    }
+    x = wave_scan_add(x);
     __syncthreads();  // protect wsum against a previous use
     if (lane == 63) wsum[wave] = x;
     __syncthreads();
@@ -276,24 +311,14 @@ __device__ void find_bins(const uint32_t *hist, SelCtrl *ctrl, int j)
         uint32_t sum = 0;
 #pragma unroll 16
         for (int k = 0; k < BPL; ++k) sum += load_u32(&hj[kSelBins - 1 - (lane * BPL + k)]);
-        uint32_t incl = sum;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t y = __shfl_up(incl, d);
-            if (lane >= d) incl += y;
-        }
+        const uint32_t incl = wave_scan_add(sum);
         const uint64_t hit = __ballot(incl - sum < need && need <= incl);
         if (hit == 0) return;  // fewer than `need` keys in all (never: need <= number of elements)
         const int seg = __ffsll((unsigned long long)hit) - 1;
-        const uint32_t seg_above = __shfl(incl - sum, seg);
+        const uint32_t seg_above = (uint32_t)__builtin_amdgcn_readlane((int)(incl - sum), seg);
         const uint32_t bin = kSelBins - 1 - (seg * BPL + (lane & 31));
         const uint32_t own = lane < 32 ? load_u32(&hj[bin]) : 0u;
-        uint32_t in2 = own;
-#pragma unroll
-        for (int d = 1; d < 32; d <<= 1) {
-            const uint32_t y = __shfl_up(in2, d);
-            if (lane >= d) in2 += y;
-        }
+        const uint32_t in2 = wave_scan_add(own);  // lanes 32.. hold zeros and are not looked at
         const uint32_t above = seg_above + in2 - own;
         if (lane < 32 && above < need && need <= above + own) {  // exactly one lane
             if (LEVEL == 1) {
@@ -319,7 +344,7 @@ __device__ __forceinline__ void wave_append(bool pred, T item, T *list, uint32_t
     const int leader = __ffsll((unsigned long long)mask) - 1;
     uint32_t base = 0;
     if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(mask));
-    base = __shfl(base, leader);
+    base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
     if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = item;
 }
 
@@ -518,12 +543,7 @@ __global__ __launch_bounds__(kThreads) void refine(SelCtrl *ctrl, uint64_t *cand
                 own[k] = h[255 - (lane * 4 + k)];
                 sum += own[k];
             }
-            uint32_t incl = sum;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t y = __shfl_up(incl, d);
-                if (lane >= d) incl += y;
-            }
+            const uint32_t incl = wave_scan_add(sum);
             uint32_t above = incl - sum;
             if (above < need && need <= incl) {
 #pragma unroll
@@ -686,10 +706,17 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
     __shared__ uint64_t red[2][3][kThreads / 64];  // per-wave (count, and, or), two generations
     __shared__ uint32_t h[3][256];                 // digit histograms, three generations
     __shared__ uint32_t nsel_ctr;
+    constexpr int kDirect = 128;                   // a threshold bin this small is ranked directly
+    __shared__ uint64_t small[kDirect];
+    __shared__ uint64_t small_thr;
+    __shared__ uint32_t small_n;
 
     for (int i = threadIdx.x; i < kHashSlots; i += kThreads) table[i] = kEmpty;
     if (threadIdx.x < 256) h[0][threadIdx.x] = h[1][threadIdx.x] = h[2][threadIdx.x] = 0;
-    if (threadIdx.x == 0) nsel_ctr = 0;
+    if (threadIdx.x == 0) {
+        nsel_ctr = 0;
+        small_n = 0;
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     uint64_t key[kKeysPerThread];
@@ -729,13 +756,9 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
             }
         }
         // block-wide count, AND and OR of the free keys: one exchange through LDS
-        uint64_t c64 = nfree;
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) {
-            c64 += __shfl_xor(c64, d);
-            vand &= __shfl_xor(vand, d);
-            vor |= __shfl_xor(vor, d);
-        }
+        const uint64_t c64 = wave_total(wave_scan_add(nfree));
+        vand = wave_and64(vand);
+        vor = wave_or64(vor);
         if (lane == 0) {
             red[gen][0][wave] = c64;
             red[gen][1][wave] = vand;
@@ -765,6 +788,7 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
             uint64_t pmask = shift + 8 >= 64 ? 0ull : ~0ull << (shift + 8);
             uint64_t prefix = all_and & pmask;
             uint32_t need = take;
+            bool direct = false;
             while (true) {
                 uint32_t *hc = h[hgen];
                 if (threadIdx.x < 256) h[(hgen + 1) % 3][threadIdx.x] = 0;
@@ -779,12 +803,7 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
                     own[k] = hc[255 - (lane * 4 + k)];
                     sum += own[k];
                 }
-                uint32_t incl = sum;
-#pragma unroll
-                for (int d = 1; d < 64; d <<= 1) {
-                    const uint32_t y = __shfl_up(incl, d);
-                    if (lane >= d) incl += y;
-                }
+                const uint32_t incl = wave_scan_add(sum);
                 uint32_t above = incl - sum;
                 uint32_t found = 0;  // digit | inside << 8 (inside <= kCandCap) ; above kept separately
                 uint32_t found_above = 0;
@@ -800,18 +819,40 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
                 }
                 const uint64_t who = __ballot(found != 0);
                 const int src_lane = __ffsll((unsigned long long)who) - 1;
-                found = __shfl(found, src_lane);
-                found_above = __shfl(found_above, src_lane);
+                found = (uint32_t)__builtin_amdgcn_readlane((int)found, src_lane);
+                found_above = (uint32_t)__builtin_amdgcn_readlane((int)found_above, src_lane);
                 const uint32_t digit = found & 255u, inside = (found >> 8) & 0x7FFFFFu;
                 hgen = (hgen + 1) % 3;
                 prefix |= (uint64_t)digit << shift;
                 pmask |= 255ull << shift;
                 need -= found_above;
                 if (need == inside || shift == 0) break;  // the whole digit bin is taken
-                shift = shift >= 8 ? shift - 8 : 0;       // the last digit may overlap the one before: harmless
+                if (inside <= (uint32_t)kDirect) {
+                    direct = true;  // few keys left in the bin: rank them against each other instead
+                    break;
+                }
+                shift = shift >= 8 ? shift - 8 : 0;  // the last digit may overlap the one before: harmless
             }
             thr = prefix;
-            // leave the generation after the last one used clean for the next kernel
+            if (direct) {  // uniform
+                // The bin's keys go to a list; key i is the threshold if exactly need - 1 of the others
+                // are larger (keys are distinct).  Two barriers instead of up to seven more passes when
+                // the cut falls inside a plateau of equal pooled scores, where only index bits differ.
+#pragma unroll
+                for (int k = 0; k < kKeysPerThread; ++k)
+                    if (((free_mask >> k) & 1u) && (key[k] & pmask) == prefix) small[atomicAdd(&small_n, 1u)] = key[k];
+                __syncthreads();
+                const uint32_t ns = small_n;  // == inside
+                if (threadIdx.x < ns) {
+                    const uint64_t mine = small[threadIdx.x];
+                    uint32_t larger = 0;
+                    for (uint32_t i = 0; i < ns; ++i) larger += small[i] > mine ? 1u : 0u;
+                    if (larger == need - 1) small_thr = mine;
+                }
+                __syncthreads();
+                thr = small_thr;
+                if (threadIdx.x == 0) small_n = 0;  // next use lies behind the barrier that ends this kernel size
+            }
         }
 
         // take every free key >= thr: one slot reservation per wavefront
@@ -820,15 +861,10 @@ __global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const 
         for (int k = 0; k < kKeysPerThread; ++k)
             if (((free_mask >> k) & 1u) && key[k] >= thr) take_mask |= 1u << k;
         const uint32_t mine = (uint32_t)__popc(take_mask);
-        uint32_t incl = mine;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t y = __shfl_up(incl, d);
-            if (lane >= d) incl += y;
-        }
+        const uint32_t incl = wave_scan_add(mine);
         uint32_t base = 0;
         if (lane == 63 && incl) base = atomicAdd(&nsel_ctr, incl);
-        uint32_t pos = __shfl(base, 63) + incl - mine;
+        uint32_t pos = (uint32_t)__builtin_amdgcn_readlane((int)base, 63) + incl - mine;
 #pragma unroll
         for (int k = 0; k < kKeysPerThread; ++k) {
             if ((take_mask >> k) & 1u) {
