@@ -9,8 +9,7 @@ import numpy as np
 
 from .allocation import (allocate, allocate_max_avg, avg_pool_same, max_pool_same, max_pool_strided, split_budget,
                          thresholds, thresholds_max_avg)
-from .rerope import (PAIR_HALF, PAIR_INTERLEAVED, chunk_bounds, chunk_distances, default_inv_freq, logits_dca,
-                     rerope_keys, rotate, round_bf16, scores_dca)
+from .rerope import PAIR_HALF, PAIR_INTERLEAVED, chunk_bounds, chunk_distances, default_inv_freq, rerope_keys, rotate
 from .scoring import MODE_MAX, MODE_SUM, num_threads, row_stats, scores
 
 
@@ -30,5 +29,5 @@ def recall_max_avg(q, k, max_kernels, avg_kernels, budget, sink=0, scale=None, m
     return idx, score
 
 
-__all__ = ["logits_dca", "scores_dca", "round_bf16", "rerope_keys", "rotate", "chunk_bounds", "chunk_distances", "default_inv_freq", "PAIR_HALF", "PAIR_INTERLEAVED", "recall_max_avg", "thresholds_max_avg", "allocate", "allocate_max_avg", "avg_pool_same", "max_pool_strided", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
+__all__ = ["rerope_keys", "rotate", "chunk_bounds", "chunk_distances", "default_inv_freq", "PAIR_HALF", "PAIR_INTERLEAVED", "recall_max_avg", "thresholds_max_avg", "allocate", "allocate_max_avg", "avg_pool_same", "max_pool_strided", "max_pool_same", "split_budget", "thresholds", "scores", "row_stats",
            "num_threads", "recall", "MODE_SUM", "MODE_MAX"]

@@ -20,12 +20,6 @@ Readings taken where the paper is silent:
     frequencies); pair j is (x[j], x[j + d/2]) in the half-split layout of the Llama family
     (PAIR_HALF, default) or (x[2j], x[2j+1]) in the interleaved layout (PAIR_INTERLEAVED);
   * the result is returned unrounded (fp64); a bf16 cache is compared after rounding.
-
-Query-side form (`logits_dca`, `scores_dca`): R(D) is orthogonal, so q . (R(D_i) k) = (R(-D_i) q) . k.
-The recall step may therefore leave the cache as it is and score the tokens of chunk i with the
-query states turned by -D_i.  In exact arithmetic the two forms give the same logits; with a bf16
-cache the one rounding to bf16 falls on the turned query instead of on the turned key, and that is
-what this form's oracle does (fp32 inputs are not rounded at all).
 """
 from __future__ import annotations
 
@@ -103,52 +97,3 @@ def rerope_keys(k: np.ndarray, chunk: int, first_extra: int = 0, base: float = 1
         if dist:
             out[:, start:end, :] = rotate(x[:, start:end, :], dist, freq, pairing)
     return out
-
-
-def round_bf16(x: np.ndarray) -> np.ndarray:
-    """fp64 values rounded to the nearest bf16 value (8 significant bits, ties to even), returned as
-    fp64.  Normal range only: no subnormals, no overflow handling."""
-    x = np.asarray(x, dtype=np.float64)
-    m, e = np.frexp(x)                      # x = m * 2^e, 0.5 <= |m| < 1
-    return np.ldexp(np.rint(m * 256.0), e - 8)  # rint rounds halves to even
-
-
-def logits_dca(q: np.ndarray, k: np.ndarray, chunk: int, first_extra: int = 0, base: float = 10000.0,
-               inv_freq: Optional[np.ndarray] = None, pairing: int = PAIR_HALF,
-               scale: Optional[float] = None) -> np.ndarray:
-    """Scaled logits [Hq, Lq, L] (fp64) of Eq. 4 with the second DCA equation applied on the query
-    side: tokens of chunk i meet R(-D_i) q.  q, k: float32 or uint16 bf16 bit patterns (then the turned
-    query is rounded to bf16, as a kernel that feeds it to a bf16 matrix unit must)."""
-    if q.ndim != 3 or k.ndim != 3 or q.shape[2] != k.shape[2] or q.dtype != k.dtype:
-        raise ValueError("q is [Hq, Lq, d], k is [Hkv, L, d], same element type")
-    Hq, Lq, d = q.shape
-    Hkv, L, _ = k.shape
-    if Hq % Hkv:
-        raise ValueError("Hq must be a multiple of Hkv")
-    G = Hq // Hkv
-    freq = default_inv_freq(d, base) if inv_freq is None else np.asarray(inv_freq, dtype=np.float64)
-    scale = 1.0 / np.sqrt(d) if scale is None else float(scale)
-    qw, kw = _widen(q), _widen(k)
-    bounds = chunk_bounds(L, chunk, first_extra)
-    out = np.empty((Hq, Lq, L), dtype=np.float64)
-    for (start, end), dist in zip(bounds, chunk_distances(len(bounds), chunk)):
-        qc = qw
-        if dist:
-            qc = rotate(qw, -dist, freq, pairing)
-            if q.dtype == np.uint16:
-                qc = round_bf16(qc)
-        for h in range(Hq):
-            out[h, :, start:end] = (qc[h] @ kw[h // G, start:end].T) * scale
-    return out
-
-
-def scores_dca(q: np.ndarray, k: np.ndarray, chunk: int, first_extra: int = 0, base: float = 10000.0,
-               inv_freq: Optional[np.ndarray] = None, pairing: int = PAIR_HALF,
-               scale: Optional[float] = None, mode_max: bool = False) -> np.ndarray:
-    """score[L] (fp64): softmax of `logits_dca` over all L positions per (head, query) (Eq. 4), then the
-    sum (or the maximum) over heads and queries (Eq. 5)."""
-    s = logits_dca(q, k, chunk, first_extra, base, inv_freq, pairing, scale)
-    s -= s.max(axis=2, keepdims=True)
-    np.exp(s, out=s)
-    s /= s.sum(axis=2, keepdims=True)
-    return s.max(axis=(0, 1)) if mode_max else s.sum(axis=(0, 1))
