@@ -100,3 +100,26 @@ def test_bf16_bit_patterns_and_custom_frequencies():
     b = oracle.rerope_keys(exact, 8, 0, inv_freq=freq)
     assert np.array_equal(a, b)
     np.testing.assert_allclose(a[0, 0], _complex_rope(exact[0, 0], 3 * 8, freq, oracle.PAIR_HALF), atol=1e-12)
+
+
+@pytest.mark.parametrize("pairing", [oracle.PAIR_HALF, oracle.PAIR_INTERLEAVED])
+def test_turning_the_key_equals_turning_the_query_back(pairing):
+    """R(D) is orthogonal: q . (R(D) k) = (R(-D) q) . k.  Pins the direction of the rotation of every
+    chunk of `rerope_keys` from the other operand's side."""
+    rng = np.random.default_rng(11)
+    L, chunk, extra, d = 97, 16, 4, 16
+    q = rng.standard_normal((3, d))
+    k = rng.standard_normal((2, L, d)).astype(np.float32)
+    freq = oracle.default_inv_freq(d, 100.0)
+    kr = oracle.rerope_keys(k, chunk, extra, base=100.0, pairing=pairing)
+    bounds = oracle.chunk_bounds(L, chunk, extra)
+    turned = 0
+    for (s0, e0), dist in zip(bounds, oracle.chunk_distances(len(bounds), chunk)):
+        qc = oracle.rotate(q, -dist, freq, pairing)
+        want = np.einsum("id,htd->hit", qc, k[:, s0:e0].astype(np.float64))
+        got = np.einsum("id,htd->hit", q, kr[:, s0:e0])
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+        if dist:
+            plain = np.einsum("id,htd->hit", q, k[:, s0:e0].astype(np.float64))
+            turned += int(np.abs(got - plain).max() > 0.1)
+    assert turned >= 3
