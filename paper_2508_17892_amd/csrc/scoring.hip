@@ -109,7 +109,7 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 __device__ __forceinline__ void lds_dma16(i32x4 rsrc, unsigned lds_addr, int voffset)
 {
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voffset), "s"(rsrc)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ float quad_swap1(float x)  // lanes 0<->1, 2<->3 of every quad
