@@ -217,8 +217,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         const int row = pchunk / CPR, cpos = pchunk % CPR;
         dma_voff[j] = (int)(row * krow_bytes) + (cpos ^ (row & 15)) * 16;
     }
+    // Pass 2 walks its split backwards: pass 1 has just streamed the same split forwards, so what it read
+    // last is what the memory-side cache still holds (an eighth of K at 1M tokens).  `tile` counts in
+    // processing order everywhere; only the two places that turn it into tokens go through here.
+    auto first_token = [&](int64_t tile) { return (MODE == 1 ? tile0 + tile1 - 1 - tile : tile) * TN; };
     auto issue_tile = [&](int64_t tile, int buf) {
-        const int64_t tok0 = tile * TN;
+        const int64_t tok0 = first_token(tile);
         const unsigned long long base = (unsigned long long)(kbase + tok0 * krow_bytes);
         long long avail = (a.L - tok0 - 1) * krow_bytes + ROWB;  // bytes up to the end of row L-1
         if (avail > 0xFFFFFFFFll) avail = 0xFFFFFFFFll;
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         acc = RMAX ? fmaxf(acc, x1) : acc + x1;
         const float x2 = quad_swap2(acc);
         acc = RMAX ? fmaxf(acc, x2) : acc + x2;
-        const int64_t tok = tile * TN + tl;
+        const int64_t tok = first_token(tile) + tl;
         // after the quad reduction the four lanes of a token hold the same value and all store it
         float *dst = (live && tok < a.L) ? a.partial + ((int64_t)unit * a.L + tok) : a.dump + (lane & 15);
         *dst = acc;
