@@ -28,6 +28,9 @@ SHAPES = [
     ("f32_two_query_blocks", 2100, 48, 8, 2, "f32", True),     # 192 rows/group: 2 query blocks of 128
     ("bf16_single_token", 1, 4, 4, 2, "bf16", False),
     ("bf16_exact_tiles", 4096, 32, 32, 8, "bf16", False),
+    # head counts of the other models the paper evaluates (Section 4): GQA groups of 7 and of 8
+    ("qwen2_5_7b_heads", 3000, 64, 28, 4, "bf16", True),       # 448 rows/group: one 8-wave query block, 64 rows padded
+    ("qwen3_32b_heads", 2500, 40, 64, 8, "bf16", True),        # 320 rows/group: two 4-wave query blocks
 ]
 
 
