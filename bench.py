@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_MFMA_TFLOPS = 157.3  # fp32 matrix path (cfg 1 only)
 # HBM bytes per launch of the dominant scoring kernel, from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE
 # scaled by the 256 MiB copy (profiles/score_kernel_cfg5_1m_hbm_traffic.md); algorithmic: 2 GiB of K.
-MEASURED_TRAFFIC_BYTES = {5: {0: 2.166e9, 1: 2.239e9}}
+MEASURED_TRAFFIC_BYTES = {5: {0: 2.166e9, 1: 2.232e9}}
 
 
 def main() -> int:
