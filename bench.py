@@ -16,13 +16,57 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_MFMA_TFLOPS = 157.3  # fp32 matrix path (cfg 1 only)
 # HBM bytes per launch of the dominant scoring kernel, from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE
 # scaled by the 256 MiB copy (profiles/score_kernel_cfg5_1m_hbm_traffic.md); algorithmic: 2 GiB of K.
 MEASURED_TRAFFIC_BYTES = {5: {0: 2.166e9, 1: 2.232e9}}
+
+
+def mfma_ceiling(il, torch, launches: int = 5, iters: int = 2000) -> dict:
+    """Register-only loops (ilre_probe_mfma_ceiling) on random and on constant bf16 operands: TFLOP/s from HIP events,
+    the shader clock from the cycle and 100 MHz counters each workgroup reads at its start and end."""
+    out = torch.empty(il.ILRE_PROBE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    operand_sets = {"random": torch.randn(il.ILRE_PROBE_OPERAND_BYTES // 2, device="cuda", generator=g).to(torch.bfloat16),
+                    "constant": torch.ones(il.ILRE_PROBE_OPERAND_BYTES // 2, device="cuda", dtype=torch.bfloat16)}
+    rows = []
+    variant = 0
+    while il.ilre_probe_describe(variant) is not None:
+        for name, ops in operand_sets.items():
+            if name == "constant" and variant > 1:
+                continue
+            for _ in range(2):
+                flops = il.ilre_probe_mfma_ceiling(variant, iters, ops, out)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(launches):
+                il.ilre_probe_mfma_ceiling(variant, iters, ops, out)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / launches
+            clk = out[1 << 20:(1 << 20) + 4096].view(torch.int64).view(256, 2).double().cpu()
+            ghz = float((clk[:, 0] / clk[:, 1]).mean()) * 0.1          # cycles per 10 ns tick
+            tf = flops / (ms * 1e-3) / 1e12
+            rows.append({"variant": variant, "what": il.ilre_probe_describe(variant), "operands": name,
+                         "ms": round(ms, 4), "tflops": round(tf, 1), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                         "clock_ghz": round(ghz, 3),
+                         # the MFMA pipe's share of the cycles at the measured clock; for the loops without MFMAs,
+                         # the same ratio for the MFMAs that were left out (above 1: the vector work alone is faster)
+                         "mfma_busy": round(tf / (PEAK_BF16_TFLOPS * ghz / 2.4), 4) if ghz > 0 else None})
+        variant += 1
+    def pick(v, o):
+        return next(r["tflops"] for r in rows if r["variant"] == v and r["operands"] == o)
+    mix = max(r["tflops"] for r in rows if r["operands"] == "random" and r["variant"] in (1, 3, 6))
+    return {"what": "register-only loops: 8 bf16 MFMAs 32x32x16 per 32x32 block, per logit fma + exp2 + add on the block "
+                    "before (the scoring kernels' mix); no LDS, no loads, no barriers; one workgroup per CU",
+            "iters": iters, "launches": launches,
+            "mix_random_tflops": mix, "mix_random_frac_of_peak": round(mix / PEAK_BF16_TFLOPS, 4),
+            "mfma_only_random_tflops": pick(0, "random"), "mfma_only_constant_tflops": pick(0, "constant"),
+            "rows": rows}
 
 
 def main() -> int:
@@ -44,6 +88,10 @@ def main() -> int:
     ap.add_argument("--no-rerope", action="store_true", help="skip the leg that times the DCA re-RoPE of the key cache")
     ap.add_argument("--no-paper-allocation", action="store_true",
                     help="skip the leg that times the whole step with Algorithm 1 as printed (48 max/average combinations)")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the leg that measures what register-only MFMA loops with the scoring kernels' "
+                         "instruction mix reach on this GPU (the ceiling the roofline fraction is to be read against)")
+    ap.add_argument("--mfma-ceiling-only", action="store_true", help="run only that leg (for rocprofv3 --pmc runs)")
     ap.add_argument("--gemm-context", action="store_true",
                     help="also time a library bf16 GEMM (8192^3, random operands) as context for the MFMA roofline")
     args = ap.parse_args()
@@ -57,12 +105,15 @@ def main() -> int:
 
     import inputs
     import paper_2508_17892_amd as il
-    from parity import to_device
+    to_device = il.to_device
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     il.load()  # fails loudly if the HIP library is not built
+    if args.mfma_ceiling_only:
+        print(json.dumps({"mfma_ceiling": mfma_ceiling(il, torch)}))
+        return 0
 
     wl = inputs.CONFIGS[args.config]
     t0 = time.time()
@@ -231,6 +282,12 @@ def main() -> int:
                                    "frac": round(alg / (sel_ms * 1e-3) / 1e9 / 8000.0, 4),
                                    "note": "ilre_select alone on 2^27 synthetic scores; algorithmic bytes = n*4L + 4B"}
         del big, ws_s
+
+    if not args.no_mfma_ceiling:
+        result["mfma_ceiling"] = mfma_ceiling(il, torch)
+        if result["roofline"]["bound"] == "mfma":
+            result["roofline"]["frac_of_measured_ceiling"] = round(result["roofline"]["achieved"] /
+                                                                   result["mfma_ceiling"]["mix_random_tflops"], 4)
 
     if args.gemm_context:
         n = 8192

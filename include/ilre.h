@@ -75,6 +75,7 @@ typedef enum { ILRE_ROPE_HALF = 0, ILRE_ROPE_INTERLEAVED = 1 } ilre_rope_pairing
 #define ILRE_MAX_POOL_KERNELS 64 /* most kernel sizes (or max/average combinations) in one call */
 #define ILRE_MAX_MAX_KERNEL 1024 /* largest strided max-pooling kernel (the *_max_avg entry points) */
 #define ILRE_MAX_AVG_KERNEL 1024 /* largest average-pooling kernel */
+#define ILRE_STATIC_SCRATCH_BYTES (4u << 20) /* scratch built into the library for ilre_row_stats_static, per GPU */
 
 typedef struct {
     int32_t struct_size;     /* sizeof(ilre_opts), for versioning */
@@ -117,6 +118,19 @@ int ilre_recall(const void *q, const void *k_cache,
 int ilre_row_stats(const void *q, const void *k_cache,
                    int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                    float *row_ref, float *row_sumexp, const ilre_opts *opts);
+
+/* ilre_row_stats for callers that cannot allocate device memory or pass a workspace: code running under HIP
+   graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+   bit-identical results; the per-split partial statistics and the overflow flag live in a buffer of
+   ILRE_STATIC_SCRATCH_BYTES built into the library (one copy per GPU, held until the process ends) instead
+   of opts->workspace, which is not read.  Makes no allocating call.  ILRE_EUNSUPPORTED when the shape needs
+   more scratch than the buffer holds (2 * 4 bytes per query row and token split, plus 512; the 1M-token
+   workload with 8192 rows needs 1 MiB).  Every call on a GPU shares that GPU's buffer: calls that overlap
+   on one GPU (different streams, or different threads without ordering) race; calls ordered on one stream
+   do not.  Nothing in the buffer needs to start at zero and nothing of an earlier call is read. */
+int ilre_row_stats_static(const void *q, const void *k_cache,
+                          int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                          float *row_ref, float *row_sumexp, const ilre_opts *opts);
 
 /* Stage 2 (Eq. 4 normalised, Eq. 5): recompute the logits, normalise with the given row
    statistics (any pair with the right row_ref + log row_sumexp) and reduce over heads and queries.
@@ -185,6 +199,23 @@ int ilre_gather_ids(const int32_t *input_ids, int64_t L, const int32_t *idx, int
 int ilre_rerope_keys(const void *k_in, void *k_out, int64_t L, int32_t Hkv, int32_t d,
                      int32_t chunk_tokens, int32_t first_extra, double rope_base, const double *inv_freq,
                      int32_t pairing, const ilre_opts *opts);
+
+/* Measurement aid, not a step of the method: register-only loops with the instruction mix of the two scoring
+   passes (Section 3.2, Eq. 4 / Eq. 5: 8 bf16 MFMAs per 32x32 block of logits; one fma, one exp2 and one add per
+   logit), no LDS, no loads and no barriers inside the loop, one workgroup per compute unit.  The rate such a
+   loop reaches on the caller's operands bounds what the scoring kernels can reach on the same chip.
+   variant    0 .. (number of variants - 1); ilre_probe_describe(variant) names it, NULL past the last one
+   iters      loop iterations per wavefront (>= 1); one iteration is 2 units of 8 MFMAs per 32 query rows
+   operands   dev  ILRE_PROBE_OPERAND_BYTES of bf16 values the MFMA fragments are read from (once, before the loop)
+   out        dev  ILRE_PROBE_OUT_BYTES, 256-byte aligned: 1 MiB of floats nobody needs (they keep the loop alive),
+                   then per workgroup two uint64: shader clock cycles and 100 MHz wall ticks the workgroup ran for
+   out_flops  host the MFMA flops of the launch
+   Needs no workspace; opts supplies the stream. */
+#define ILRE_PROBE_OPERAND_BYTES 65536
+#define ILRE_PROBE_OUT_BYTES ((1u << 20) + 4096)
+int ilre_probe_mfma_ceiling(int32_t variant, int32_t iters, const void *operands, void *out, double *out_flops,
+                            const ilre_opts *opts);
+const char *ilre_probe_describe(int32_t variant);
 
 /* Message for the last non-OK status returned to the calling thread (static storage, never NULL). */
 const char *ilre_last_error(void);

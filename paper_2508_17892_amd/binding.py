@@ -26,9 +26,11 @@ ILRE_MAX_POOL_KERNELS = 64
 ILRE_MAX_MAX_KERNEL = 1024
 ILRE_MAX_AVG_KERNEL = 1024
 
-EXPORTS = ("ilre_workspace_bytes", "ilre_recall", "ilre_row_stats", "ilre_col_scores", "ilre_select",
+ILRE_STATIC_SCRATCH_BYTES = 4 << 20
+
+EXPORTS = ("ilre_workspace_bytes", "ilre_recall", "ilre_row_stats", "ilre_row_stats_static", "ilre_col_scores", "ilre_select",
            "ilre_select_max_avg", "ilre_recall_max_avg", "ilre_workspace_bytes_max_avg", "ilre_rerope_keys",
-           "ilre_gather_ids", "ilre_last_error")
+           "ilre_gather_ids", "ilre_probe_mfma_ceiling", "ilre_probe_describe", "ilre_last_error")
 
 
 class IlreOpts(ctypes.Structure):
@@ -73,6 +75,8 @@ def load() -> ctypes.CDLL:
         lib.ilre_recall.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, ctypes.POINTER(i32), vp, vp, po]
         lib.ilre_row_stats.restype = ctypes.c_int
         lib.ilre_row_stats.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, po]
+        lib.ilre_row_stats_static.restype = ctypes.c_int
+        lib.ilre_row_stats_static.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, po]
         lib.ilre_col_scores.restype = ctypes.c_int
         lib.ilre_col_scores.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, po]
         lib.ilre_select.restype = ctypes.c_int
@@ -90,10 +94,22 @@ def load() -> ctypes.CDLL:
                                          i32, po]
         lib.ilre_gather_ids.restype = ctypes.c_int
         lib.ilre_gather_ids.argtypes = [vp, i64, vp, i32, vp, po]
+        lib.ilre_probe_mfma_ceiling.restype = ctypes.c_int
+        lib.ilre_probe_mfma_ceiling.argtypes = [i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), po]
+        lib.ilre_probe_describe.restype = ctypes.c_char_p
+        lib.ilre_probe_describe.argtypes = [i32]
         lib.ilre_last_error.restype = ctypes.c_char_p
         lib.ilre_last_error.argtypes = []
         _lib = lib
     return _lib
+
+
+def to_device(arr, device="cuda") -> torch.Tensor:
+    """Host array (float32, or uint16 holding bf16 bit patterns) -> device tensor of the same bits."""
+    import numpy as np
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(arr).to(device)
 
 
 def ilre_last_error() -> str:
@@ -200,6 +216,19 @@ def ilre_row_stats(q: torch.Tensor, k_cache: torch.Tensor, *, scale: float = 0.0
     _check(load().ilre_row_stats(q.data_ptr(), k_cache.data_ptr(), L, Lq, Hq, Hkv, d, row_max.data_ptr(),
                                  row_sumexp.data_ptr(), ctypes.byref(o)))
     return row_max, row_sumexp
+
+
+def ilre_row_stats_static(q: torch.Tensor, k_cache: torch.Tensor, row_ref: torch.Tensor, row_sumexp: torch.Tensor, *,
+                          scale: float = 0.0, flags: int = 0) -> None:
+    """ilre_row_stats into the caller's float32[Hq*Lq] outputs, with the library's built-in scratch buffer:
+    this wrapper and the call beneath it allocate nothing."""
+    L, Lq, Hq, Hkv, d = _qk_meta(q, k_cache)
+    for t in (row_ref, row_sumexp):
+        if t.dtype != torch.float32 or t.numel() != Hq * Lq or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("row_ref and row_sumexp must be contiguous float32 device vectors of Hq*Lq entries")
+    o = _opts(_dtype_code(q), 0, scale, ILRE_SCORE_SUM, None, q, k_cache, flags)
+    _check(load().ilre_row_stats_static(q.data_ptr(), k_cache.data_ptr(), L, Lq, Hq, Hkv, d, row_ref.data_ptr(),
+                                        row_sumexp.data_ptr(), ctypes.byref(o)))
 
 
 def ilre_col_scores(q: torch.Tensor, k_cache: torch.Tensor, row_max: torch.Tensor, row_sumexp: torch.Tensor, *,
@@ -330,3 +359,26 @@ def ilre_gather_ids(input_ids: torch.Tensor, idx: torch.Tensor, out: Optional[to
     _check(load().ilre_gather_ids(input_ids.data_ptr(), input_ids.numel(), idx.data_ptr(), idx.numel(), out.data_ptr(),
                                   ctypes.byref(o)))
     return out
+
+
+ILRE_PROBE_OPERAND_BYTES = 65536
+ILRE_PROBE_OUT_BYTES = (1 << 20) + 4096
+
+
+def ilre_probe_describe(variant: int) -> Optional[str]:
+    text = load().ilre_probe_describe(int(variant))
+    return text.decode() if text else None
+
+
+def ilre_probe_mfma_ceiling(variant: int, iters: int, operands: torch.Tensor, out: torch.Tensor) -> float:
+    """Enqueue one launch of a register-only MFMA loop (measurement aid); returns the MFMA flops of the launch.
+    `out` (uint8, ILRE_PROBE_OUT_BYTES) receives, from byte 1 MiB on, per workgroup (shader cycles, 100 MHz ticks)."""
+    if operands.numel() * operands.element_size() < ILRE_PROBE_OPERAND_BYTES or not operands.is_cuda:
+        raise ValueError("operands must hold ILRE_PROBE_OPERAND_BYTES on the device")
+    if out.numel() * out.element_size() < ILRE_PROBE_OUT_BYTES or not out.is_cuda:
+        raise ValueError("out must hold ILRE_PROBE_OUT_BYTES on the device")
+    o = _opts(ILRE_BF16, 0, 0.0, ILRE_SCORE_SUM, None)
+    flops = ctypes.c_double(0.0)
+    _check(load().ilre_probe_mfma_ceiling(int(variant), int(iters), operands.data_ptr(), out.data_ptr(), ctypes.byref(flops),
+                                          ctypes.byref(o)))
+    return float(flops.value)

@@ -5,7 +5,15 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "ilre_internal.h"
+
+// Scratch of ilre_row_stats_static: the per-split partial row statistics and the overflow flag live here
+// instead of in a caller's workspace.  One copy per GPU the library runs on, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; the device address it yields is what
+// the kernels are given.
+static __device__ __align__(256) unsigned char scratch[ILRE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -202,6 +210,64 @@ int hip_fail(hipError_t e, const char *what)
     return fail(ILRE_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// Device address of the static scratch array on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(ILRE_EUNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return fail(ILRE_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return ILRE_OK;
+}
+
+// Eq. 4 row statistics with the partial results in `scratch_base` (scratch_bytes long; a caller's workspace or
+// the static array).  static_buf only words the error message.
+int row_stats_into(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                   float *row_max, float *row_sumexp, const ilre_opts *opts, bool static_buf)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
+    if (!row_max || !row_sumexp) return fail(ILRE_EINVAL, "row_max or row_sumexp is null");
+    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
+    const int64_t nrows = (int64_t)Hq * Lq;
+    const Layout lay = make_layout(p, L, nrows, window_job(L, 1, nullptr, 0));
+    unsigned char *ws;
+    if (static_buf) {
+        if (lay.row_max > (size_t)ILRE_STATIC_SCRATCH_BYTES)
+            return fail(ILRE_EUNSUPPORTED, "this shape needs %zu bytes of scratch, the static buffer holds %zu; use ilre_row_stats",
+                        lay.row_max, (size_t)ILRE_STATIC_SCRATCH_BYTES);
+        void *ptr = nullptr;
+        if ((rc = static_scratch(&ptr))) return rc;
+        ws = (unsigned char *)ptr;
+    } else {
+        if ((rc = check_workspace(opts, lay.row_max))) return rc;
+        ws = (unsigned char *)opts->workspace;
+    }
+    ilre::ScoreArgs a{};
+    if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    fill_plan(a, p);
+    a.part_m = (float *)(ws + lay.part_m);
+    a.part_z = (float *)(ws + lay.part_z);
+    a.overflow = (uint32_t *)(ws + lay.flag);
+    const hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
+    return ILRE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -237,24 +303,13 @@ int ilre_workspace_bytes_max_avg(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv,
 int ilre_row_stats(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                    float *row_max, float *row_sumexp, const ilre_opts *opts)
 {
-    int rc = check_opts(opts);
-    if (rc) return rc;
-    if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
-    if (!row_max || !row_sumexp) return fail(ILRE_EINVAL, "row_max or row_sumexp is null");
-    const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
-    const int64_t nrows = (int64_t)Hq * Lq;
-    const Layout lay = make_layout(p, L, nrows, window_job(L, 1, nullptr, 0));
-    if ((rc = check_workspace(opts, lay.row_max))) return rc;
-    ilre::ScoreArgs a{};
-    if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
-    fill_plan(a, p);
-    unsigned char *ws = (unsigned char *)opts->workspace;
-    a.part_m = (float *)(ws + lay.part_m);
-    a.part_z = (float *)(ws + lay.part_z);
-    a.overflow = (uint32_t *)(ws + lay.flag);
-    const hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, (hipStream_t)opts->stream);
-    if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
-    return ILRE_OK;
+    return row_stats_into(q, k_cache, L, Lq, Hq, Hkv, d, row_max, row_sumexp, opts, false);
+}
+
+int ilre_row_stats_static(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
+                          float *row_max, float *row_sumexp, const ilre_opts *opts)
+{
+    return row_stats_into(q, k_cache, L, Lq, Hq, Hkv, d, row_max, row_sumexp, opts, true);
 }
 
 int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
@@ -394,6 +449,24 @@ int ilre_rerope_keys(const void *k_in, void *k_out, int64_t L, int32_t Hkv, int3
     }
     const hipError_t e = ilre::launch_rerope(a, opts->dtype, pairing, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "re-RoPE launch");
+    return ILRE_OK;
+}
+
+const char *ilre_probe_describe(int32_t variant) { return ilre::probe_describe(variant); }
+
+int ilre_probe_mfma_ceiling(int32_t variant, int32_t iters, const void *operands, void *out, double *out_flops,
+                            const ilre_opts *opts)
+{
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if (variant < 0 || variant >= ilre::probe_variants()) return fail(ILRE_EINVAL, "no probe variant %d", variant);
+    if (iters < 1) return fail(ILRE_EINVAL, "iters must be positive");
+    if (!operands || !out || !out_flops) return fail(ILRE_EINVAL, "operands, out or out_flops is null");
+    if (((uintptr_t)operands & 15) || ((uintptr_t)out & 255)) return fail(ILRE_EINVAL, "operands must be 16-byte, out 256-byte aligned");
+    const hipError_t e = ilre::launch_probe(variant, iters, operands, (float *)out,
+                                            (unsigned long long *)((unsigned char *)out + (1u << 20)), out_flops,
+                                            (hipStream_t)opts->stream);
+    if (e != hipSuccess) return hip_fail(e, "probe launch");
     return ILRE_OK;
 }
 

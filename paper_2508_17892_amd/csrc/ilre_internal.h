@@ -143,4 +143,11 @@ struct RopeArgs {
 
 hipError_t launch_rerope(const RopeArgs &a, int dtype, int pairing, hipStream_t s);
 
+// ---------------------------------------------------------------- measurement aid: MFMA ceiling probes
+
+int probe_variants();
+const char *probe_describe(int variant);
+hipError_t launch_probe(int variant, int iters, const void *operands, float *out, unsigned long long *clocks, double *flops,
+                        hipStream_t s);
+
 }  // namespace ilre

@@ -1,13 +1,19 @@
 #!/usr/bin/env python3
-"""Writes tests/golden/fullsize_cfg{N}.json from the CPU oracle alone (imports only inputs/ and oracle/).
+"""Writes the full-size expected values of tests/golden/ from the CPU oracle alone (imports only inputs/
+and oracle/).
 
-For the workloads too large for the oracle to run inside a GPU test, the oracle is run once here and
-a compact digest is stored: sampled softmax row statistics, sampled per-token scores, the score total,
-the recalled index set, each kernel's admission threshold and the tokens the comparison rule excuses
-(oracle pooled score within 2*(1e-6 + 1e-3*thr_j) of a threshold), and the same pair (index set, excused
-tokens) for Algorithm 1 as printed with the paper's default pooling set.  Usage:
+For the workloads too large for the oracle to run inside a GPU test (cfg 4: 512K tokens, cfg 5: 1M tokens),
+the oracle is run once here and everything the GPU test compares is stored, nothing sampled:
 
-    python tests/golden/make_fullsize_golden.py 3 4 5
+    fullsize_cfg{N}_scores.npy     the oracle's per-token score of Eq. 5, all L of them, rounded to float32
+                                   (a relative 6e-8 against the 1e-3 the comparison allows)
+    fullsize_cfg{N}_rowstats.npy   float64 [2, Hq*Lq]: row maximum and sum of exponentials of Eq. 4, every row
+    fullsize_cfg{N}.json           shape, oracle wall time and thread count, the score total, and for both
+                                   forms of Algorithm 1 the recalled index set, each kernel's admission
+                                   threshold and the tokens the comparison rule excuses (oracle pooled score
+                                   within 2*(1e-6 + 1e-3*thr_j) of a threshold)
+
+Usage:    python tests/golden/make_fullsize_golden.py 4 5
 """
 from __future__ import annotations
 
@@ -25,11 +31,10 @@ import inputs  # noqa: E402
 import oracle  # noqa: E402
 
 REL_TOL, ABS_TOL = 1e-3, 1e-6
-N_ROWS, N_RANDOM_TOKENS, N_SELECTED_TOKENS = 256, 1024, 1024
 PAPER_MAX, PAPER_AVG, PAPER_SINK = (2, 4, 8), tuple(range(1, 17)), 4   # default pooling set and sink size of the paper
 
 
-def digest(cfg: int) -> dict:
+def digest(cfg: int):
     wl = inputs.CONFIGS[cfg]
     inp = inputs.generate(wl)
     t0 = time.time()
@@ -53,26 +58,17 @@ def digest(cfg: int) -> dict:
             if thr is not None:
                 with np.errstate(invalid="ignore"):
                     ma_excused |= np.abs(per_token - thr) <= 2 * (ABS_TOL + REL_TOL * abs(thr))
-    rng = np.random.default_rng(3000 + cfg)
-    rows = np.sort(rng.choice(wl.Hq * wl.Lq, size=N_ROWS, replace=False))
-    toks = np.unique(np.concatenate([rng.choice(wl.L, size=N_RANDOM_TOKENS, replace=False),
-                                     rng.choice(idx, size=min(N_SELECTED_TOKENS, idx.size), replace=False)]))
     mask = inp.needle_mask
     near = np.zeros(wl.L, dtype=bool)                      # within 15 positions of a span
     for s, n in inp.spans:
         near[max(0, s - 15):min(wl.L, s + n + 15)] = True
-    return {
-        "cite": "Section 3.2, Eq. 4 / Eq. 5 (sum reading) / Algorithm 1 (stride-1 max-pool reading); written by "
-                "tests/golden/make_fullsize_golden.py from oracle/ on inputs/ workload " + wl.name,
+    meta = {
+        "cite": "Section 3.2, Eq. 4 / Eq. 5 (sum reading) / Algorithm 1 (stride-1 max-pool reading and as printed); "
+                "written by tests/golden/make_fullsize_golden.py from oracle/ on inputs/ workload " + wl.name,
         "workload": wl.name, "cfg": cfg, "L": wl.L, "Lq": wl.Lq, "Hq": wl.Hq, "Hkv": wl.Hkv, "d": wl.d,
         "pool_kernels": list(wl.pool_kernels), "budget": wl.budget,
         "oracle_seconds": round(seconds, 1), "oracle_threads": oracle.num_threads(),
         "score_total": float(score.sum()),
-        "rows": rows.tolist(),
-        "row_max": [float(x) for x in rmax[rows]],
-        "row_sumexp": [float(x) for x in rsum[rows]],
-        "tokens": toks.tolist(),
-        "token_scores": [float(x) for x in score[toks]],
         "indices": idx.tolist(),
         "thresholds": thr_list,
         "excused_tokens": np.flatnonzero(excused).tolist(),
@@ -83,15 +79,19 @@ def digest(cfg: int) -> dict:
         "needle_recall": float(mask[idx].sum() / max(1, mask.sum())),
         "precision_within_15_of_a_span": float(near[idx].mean()),
     }
+    return meta, s32, np.stack([rmax, rsum])
 
 
 def main() -> None:
-    for cfg in [int(a) for a in sys.argv[1:]] or [3, 4, 5]:
-        d = digest(cfg)
-        path = os.path.join(ROOT, "tests", "golden", f"fullsize_cfg{cfg}.json")
+    gdir = os.path.join(ROOT, "tests", "golden")
+    for cfg in [int(a) for a in sys.argv[1:]] or [4, 5]:
+        d, s32, rowstats = digest(cfg)
+        path = os.path.join(gdir, f"fullsize_cfg{cfg}.json")
         with open(path, "w") as f:
             json.dump(d, f, separators=(",", ":"))
             f.write("\n")
+        np.save(os.path.join(gdir, f"fullsize_cfg{cfg}_scores.npy"), s32)
+        np.save(os.path.join(gdir, f"fullsize_cfg{cfg}_rowstats.npy"), rowstats)
         print(f"cfg {cfg}: oracle {d['oracle_seconds']} s on {d['oracle_threads']} threads, total {d['score_total']:.6f}, "
               f"{len(d['excused_tokens'])} excusable tokens, needle recall {d['needle_recall']:.3f}, "
               f"precision {d['precision_within_15_of_a_span']:.3f} -> {path}", flush=True)

@@ -8,19 +8,12 @@ score thr_j of the last token that kernel admitted in the oracle's run.
 from __future__ import annotations
 
 import numpy as np
-import torch
 
 import oracle
+from paper_2508_17892_amd import to_device  # noqa: F401  (re-exported for the GPU tests)
 
 REL_TOL = 1e-3
 ABS_TOL = 1e-6
-
-
-def to_device(arr: np.ndarray, device="cuda") -> torch.Tensor:
-    """Generated array (float32, or uint16 bf16 bit patterns) -> device tensor of the same bits."""
-    if arr.dtype == np.uint16:
-        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
-    return torch.from_numpy(arr).to(device)
 
 
 def score_errors(gpu_scores: np.ndarray, oracle_scores: np.ndarray):

@@ -143,3 +143,16 @@ def test_argument_errors_of_the_printed_form_rerope_and_gather():
     assert lib.ilre_gather_ids(fake, 1000, fake, -1, fake, ctypes.byref(o)) == il.ILRE_EINVAL
     assert lib.ilre_gather_ids(fake, 1000, fake, 0, fake, ctypes.byref(o)) == il.ILRE_OK   # nothing to do, nothing launched
     assert il.ilre_last_error()
+
+
+def test_row_stats_static_rejects_shapes_beyond_its_buffer():
+    """The entry point that allocates nothing holds 4 MiB of scratch; a shape that needs more is refused on
+    the host, before any device call."""
+    lib = il.load()
+    fake = ctypes.c_void_p(4096)          # never dereferenced
+    o = _opts()
+    # 64 kv heads x 16384 query tokens = 1M rows, one token split: 8 MiB of partial statistics
+    rc = lib.ilre_row_stats_static(fake, fake, 1 << 20, 16384, 64, 64, 128, fake, fake, ctypes.byref(o))
+    assert rc == il.ILRE_EUNSUPPORTED and "static buffer" in il.ilre_last_error()
+    assert lib.ilre_row_stats_static(fake, fake, 1000, 8, 8, 2, 128, None, fake, ctypes.byref(o)) == il.ILRE_EINVAL
+    assert lib.ilre_row_stats_static(fake, fake, 1000, 8, 8, 2, 64, fake, fake, ctypes.byref(o)) == il.ILRE_EUNSUPPORTED

@@ -226,6 +226,8 @@ def _end_to_end(inp, kernels, budget):
     bad, worst = score_errors(scores, want_scores)
     assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
     check_index_structure(idx, wl.L, budget)
+    # the selection is Algorithm 1 run on the scores the GPU itself produced: bit-exact, no tolerance
+    assert idx.tolist() == oracle.allocate(scores, kernels, budget).tolist()
     rep = index_set_report(idx, want_scores, kernels, budget)
     assert not rep["unexcused"], rep
     return idx, scores, rep
@@ -272,6 +274,8 @@ def _end_to_end_max_avg(inp, mk, ak, budget, sink):
     assert bad == 0, f"{bad} scores out of tolerance, worst {worst:.2f}x"
     assert (idx[:sink] == np.arange(sink)).all() and (np.diff(idx[:n].astype(np.int64)) > 0).all()
     assert (idx[n:] == -1).all() and idx[:n].max() < inp.workload.L
+    # Algorithm 1 as printed on the scores the GPU itself produced: bit-exact, no tolerance
+    assert idx[:n].tolist() == oracle.allocate_max_avg(scores, mk, ak, budget, sink=sink).tolist()
     rep = index_set_report_max_avg(idx[:n], want_scores, mk, ak, budget, sink)
     assert not rep["unexcused"], rep
     return idx[:n], rep

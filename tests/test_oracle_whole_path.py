@@ -7,7 +7,7 @@ import numpy as np
 
 import inputs
 import oracle
-from brute import brute_allocate, brute_scores
+from brute import brute_allocate, brute_allocate_max_avg, brute_scores
 
 
 def test_whole_path_brute_force():
@@ -17,6 +17,29 @@ def test_whole_path_brute_force():
     np.testing.assert_allclose(score, bs, rtol=1e-12)
     b32 = [float(np.float32(x)) for x in bs]
     assert idx.tolist() == brute_allocate(b32, (1, 3, 5), 7)
+
+
+def test_whole_path_as_printed_brute_force():
+    """recall_max_avg (Eq. 4 over all positions, Eq. 5, then Algorithm 1 as printed with a sink part) against
+    pure-Python loops: sum and max reduction, a sink that is not a multiple of any max kernel, a budget that
+    the K_m cap and the shares do not divide."""
+    for seed, (L, sink, mk, ak, budget), mode in ((4, (41, 3, (2, 4), (1, 2, 3), 11), "sum"),
+                                                   (5, (29, 1, (3,), (2, 5), 9), "max"),
+                                                   (6, (23, 4, (2, 8), (1, 4), 30), "sum")):
+        inp = inputs.custom(L=L, Lq=2, Hq=4, Hkv=2, d=8, dtype="f32", seed=seed)
+        omode = oracle.MODE_SUM if mode == "sum" else oracle.MODE_MAX
+        idx, score = oracle.recall_max_avg(inp.q, inp.k, mk, ak, budget, sink=sink, mode=omode)
+        bs = brute_scores(inp.q.astype(float).tolist(), inp.k.astype(float).tolist(), 4, 2, 2, L, 8, 1 / math.sqrt(8),
+                          mode=mode)
+        np.testing.assert_allclose(score, bs, rtol=1e-12)
+        b32 = [float(np.float32(x)) for x in bs]
+        want = brute_allocate_max_avg(b32, mk, ak, budget, sink=sink)
+        assert idx.tolist() == want
+        assert idx[:sink].tolist() == list(range(sink))            # the sink part is always kept
+        # a plausible slip -- pooling the whole score vector instead of score[sink:] -- gives another set
+        if seed == 4:
+            shifted = oracle.allocate_max_avg(np.asarray(b32, dtype=np.float32), mk, ak, budget, sink=0)
+            assert sorted(set(range(sink)) | set(shifted.tolist())) != want
 
 
 def test_planted_needles_recalled_cfg1():
