@@ -53,7 +53,7 @@ extern "C" {
 
 typedef enum {
     ILRE_OK = 0,
-    ILRE_EINVAL = 1,        /* null pointer, non-positive size, Hq % Hkv != 0, even / non-positive kernel size */
+    ILRE_EINVAL = 1,        /* null pointer, non-positive size, Hq % Hkv != 0, even / non-positive kernel size, sink outside [0, L] */
     ILRE_EUNSUPPORTED = 2,  /* head_dim != 128, unknown dtype / score mode, budget or kernel size over the limits below */
     ILRE_ENOMEM = 3,        /* workspace missing or smaller than ilre_workspace_bytes() */
     ILRE_EHIP = 4           /* a HIP call failed; see ilre_last_error() */
@@ -91,6 +91,9 @@ typedef struct {
     void *workspace;         /* dev, 256-byte aligned */
     size_t workspace_bytes;
     void *stream;            /* hipStream_t */
+    int32_t sink;            /* ilre_recall / ilre_select: leading tokens that are always kept (the sink part of
+                                Algorithm 1); the pooling sees score[sink..L) and the budget counts the other tokens */
+    int32_t reserved;        /* 0 */
 } ilre_opts;
 
 /* Bytes of device workspace any entry point needs for this shape (host computation only).
@@ -102,8 +105,10 @@ int ilre_workspace_bytes(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t
    q          dev  [Hq, Lq, d] (strides in opts), element type opts->dtype, innermost d contiguous
    k_cache    dev  [Hkv, L, d] (strides in opts; token-major [L, Hkv, d] is expressible)
    pool_kernels host, opts->n_pool_kernels odd sizes >= 1, processed in this order
-   out_idx    dev  min(budget, L) int32, ascending, unique
-   out_scores dev  L float, 16-byte aligned, the un-pooled per-token score of Eq. 5 */
+   out_idx    dev  opts->sink + min(budget, L - opts->sink) int32, ascending, unique: the sink indices
+                   0 .. sink-1, then the allocated tokens
+   out_scores dev  L float, 16-byte aligned, the un-pooled per-token score of Eq. 5 (all positions, the
+                   sink part included: the softmax of Eq. 4 runs over all L) */
 int ilre_recall(const void *q, const void *k_cache,
                 int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                 int32_t budget, const int32_t *pool_kernels,
@@ -141,7 +146,8 @@ int ilre_col_scores(const void *q, const void *k_cache,
                     float *out_scores, const ilre_opts *opts);
 
 /* Stages 3-4 (Algorithm 1): pooling, budgeted top-k with skip-allocated, ascending output.
-   scores: dev, L finite floats, 16-byte aligned.  pool_kernels: host.  out_idx: dev, min(budget, L) int32. */
+   scores: dev, L finite floats, 16-byte aligned.  pool_kernels: host.
+   out_idx: dev, opts->sink + min(budget, L - opts->sink) int32. */
 int ilre_select(const float *scores, int64_t L, int32_t budget, const int32_t *pool_kernels,
                 int32_t *out_idx, const ilre_opts *opts);
 

@@ -15,7 +15,9 @@ Readings taken where the algorithm is silent:
   * candidates are ranked by (pooled score descending, token index ascending);
   * all not-yet-allocated tokens are candidates (no top-K_m cap), so a kernel always
     finds its share while unallocated tokens remain;
-  * no sink part: I starts empty.
+  * sink part (optional, as in the printed form): the first `sink` tokens are always allocated and take
+    no part in the pooling (the scores handed to the pooling are score[sink:]); the budget B counts the
+    other tokens.  sink = 0: I starts empty.
 Decisions are taken in the precision of the array passed in (pass float32 to decide as the
 GPU path does).
 """
@@ -51,21 +53,24 @@ def split_budget(budget: int, n: int) -> List[int]:
     return [base + (1 if j < rem else 0) for j in range(n)]
 
 
-def allocate(score: np.ndarray, pool_kernels: Sequence[int], budget: int) -> np.ndarray:
-    """Algorithm 1: per kernel size pool, rank, add the first B_j tokens not yet in I;
-    return I sorted ascending (int64)."""
-    L = score.shape[0]
+def allocate(score: np.ndarray, pool_kernels: Sequence[int], budget: int, sink: int = 0) -> np.ndarray:
+    """Algorithm 1: I starts as the sink indices; per kernel size pool score[sink:], rank, add the first
+    B_j tokens not yet in I; return I sorted ascending (int64)."""
+    if sink < 0 or sink > score.shape[0]:
+        raise ValueError("sink out of range")
+    body = score[sink:]
+    L = body.shape[0]
     shares = split_budget(budget, len(pool_kernels))
     allocated = np.zeros(L, dtype=bool)
     token = np.arange(L)
     for w, share in zip(pool_kernels, shares):
-        pooled = max_pool_same(score, int(w))
+        pooled = max_pool_same(body, int(w))
         # rank every token by (pooled descending, index ascending)
         order = np.lexsort((token, -pooled.astype(np.float64)))
         free = order[~allocated[order]]
         take = free[:share]
         allocated[take] = True
-    return np.flatnonzero(allocated).astype(np.int64)
+    return np.concatenate([np.arange(sink), sink + np.flatnonzero(allocated)]).astype(np.int64)
 
 
 def thresholds(score: np.ndarray, pool_kernels: Sequence[int], budget: int):

@@ -48,6 +48,8 @@ class IlreOpts(ctypes.Structure):
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
+        ("sink", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 
@@ -152,7 +154,7 @@ def _qk_meta(q: torch.Tensor, k: torch.Tensor):
 
 
 def _opts(dtype: int, n_pool_kernels: int, scale: float, score_mode: int, workspace: Optional[torch.Tensor],
-          q: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, flags: int = 0) -> IlreOpts:
+          q: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, flags: int = 0, sink: int = 0) -> IlreOpts:
     o = IlreOpts()
     o.struct_size = ctypes.sizeof(IlreOpts)
     o.dtype = dtype
@@ -160,6 +162,7 @@ def _opts(dtype: int, n_pool_kernels: int, scale: float, score_mode: int, worksp
     o.score_mode = score_mode
     o.scale = float(scale)
     o.flags = int(flags)
+    o.sink = int(sink)
     if q is not None:
         o.q_stride_head, o.q_stride_token = q.stride(0), q.stride(1)
     if k is not None:
@@ -182,21 +185,21 @@ def _kernel_array(pool_kernels: Sequence[int]):
 
 
 def ilre_recall(q: torch.Tensor, k_cache: torch.Tensor, budget: int, pool_kernels: Sequence[int], *,
-                scale: float = 0.0, score_mode: int = ILRE_SCORE_SUM, flags: int = 0,
+                scale: float = 0.0, score_mode: int = ILRE_SCORE_SUM, flags: int = 0, sink: int = 0,
                 workspace: Optional[torch.Tensor] = None,
                 out_idx: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None
                 ) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Whole path; returns (out_idx int32[min(budget, L)] ascending, out_scores float32[L])."""
+    """Whole path; returns (out_idx int32[sink + min(budget, L - sink)] ascending, out_scores float32[L])."""
     L, Lq, Hq, Hkv, d = _qk_meta(q, k_cache)
     dt = _dtype_code(q)
     n = len(pool_kernels)
     if workspace is None:
         workspace = alloc_workspace(L, Lq, Hq, Hkv, d, n, dt, q.device)
     if out_idx is None:
-        out_idx = torch.empty(min(int(budget), L), dtype=torch.int32, device=q.device)
+        out_idx = torch.empty(int(sink) + min(int(budget), L - int(sink)), dtype=torch.int32, device=q.device)
     if out_scores is None:
         out_scores = torch.empty(L, dtype=torch.float32, device=q.device)
-    o = _opts(dt, n, scale, score_mode, workspace, q, k_cache, flags)
+    o = _opts(dt, n, scale, score_mode, workspace, q, k_cache, flags, sink)
     _check(load().ilre_recall(q.data_ptr(), k_cache.data_ptr(), L, Lq, Hq, Hkv, d, int(budget), _kernel_array(pool_kernels),
                               out_idx.data_ptr(), out_scores.data_ptr(), ctypes.byref(o)))
     return out_idx, out_scores
@@ -250,9 +253,9 @@ def ilre_col_scores(q: torch.Tensor, k_cache: torch.Tensor, row_max: torch.Tenso
     return out
 
 
-def ilre_select(scores: torch.Tensor, budget: int, pool_kernels: Sequence[int], *,
+def ilre_select(scores: torch.Tensor, budget: int, pool_kernels: Sequence[int], *, sink: int = 0,
                 workspace: Optional[torch.Tensor] = None, out_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Algorithm 1 on a float32 score vector; returns int32[min(budget, L)] ascending."""
+    """Algorithm 1 on a float32 score vector; returns int32[sink + min(budget, L - sink)] ascending."""
     if scores.dtype != torch.float32 or scores.dim() != 1 or not scores.is_contiguous() or not scores.is_cuda:
         raise ValueError("scores must be a contiguous float32 device vector")
     L = scores.numel()
@@ -261,8 +264,8 @@ def ilre_select(scores: torch.Tensor, budget: int, pool_kernels: Sequence[int], 
         # the selection region is the tail of the full workspace; sized on its own here
         workspace = alloc_workspace(L, 1, 1, 1, 128, n, ILRE_F32, scores.device)
     if out_idx is None:
-        out_idx = torch.empty(min(int(budget), L), dtype=torch.int32, device=scores.device)
-    o = _opts(ILRE_F32, n, 0.0, ILRE_SCORE_SUM, workspace)
+        out_idx = torch.empty(int(sink) + min(int(budget), L - int(sink)), dtype=torch.int32, device=scores.device)
+    o = _opts(ILRE_F32, n, 0.0, ILRE_SCORE_SUM, workspace, sink=sink)
     _check(load().ilre_select(scores.data_ptr(), L, int(budget), _kernel_array(pool_kernels), out_idx.data_ptr(),
                               ctypes.byref(o)))
     return out_idx

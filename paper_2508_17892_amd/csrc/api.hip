@@ -36,11 +36,12 @@ struct Layout {
     ilre::SelectLayout sel;
 };
 
-ilre::SelectJob window_job(int64_t L, int budget, const int32_t *pool_kernels, int n_kernels)
+ilre::SelectJob window_job(int64_t L, int sink, int budget, const int32_t *pool_kernels, int n_kernels)
 {
     ilre::SelectJob job{};
     job.mode = ilre::kSelWindowMax;
-    job.L = L;
+    job.L = L - sink;
+    job.sink = sink;
     job.budget = budget;
     job.n_max = n_kernels;
     job.n_avg = 1;
@@ -153,6 +154,8 @@ int check_opts(const ilre_opts *o)
         return fail(ILRE_EUNSUPPORTED, "unknown score_mode %d", o->score_mode);
     if (!(o->scale >= 0.f) || isinf(o->scale)) return fail(ILRE_EINVAL, "scale must be finite and >= 0 (0 = 1/sqrt(d))");
     if (o->flags & ~ILRE_FLAG_EXACT_ROW_MAX) return fail(ILRE_EUNSUPPORTED, "unknown flag bits 0x%x", o->flags);
+    if (o->sink < 0) return fail(ILRE_EINVAL, "sink must be non-negative");
+    if (o->reserved != 0) return fail(ILRE_EINVAL, "opts->reserved must be 0");
     return ILRE_OK;
 }
 
@@ -244,7 +247,7 @@ int row_stats_into(const void *q, const void *k_cache, int64_t L, int32_t Lq, in
     if (!row_max || !row_sumexp) return fail(ILRE_EINVAL, "row_max or row_sumexp is null");
     const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
     const int64_t nrows = (int64_t)Hq * Lq;
-    const Layout lay = make_layout(p, L, nrows, window_job(L, 1, nullptr, 0));
+    const Layout lay = make_layout(p, L, nrows, window_job(L, 0, 1, nullptr, 0));
     unsigned char *ws;
     if (static_buf) {
         if (lay.row_max > (size_t)ILRE_STATIC_SCRATCH_BYTES)
@@ -283,7 +286,7 @@ int ilre_workspace_bytes(int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t
     if (n_pool_kernels < 0 || n_pool_kernels > ILRE_MAX_POOL_KERNELS)
         return fail(ILRE_EINVAL, "n_pool_kernels out of range");
     const ilre::ScorePlan p = ilre::make_score_plan(dtype, L, Lq, Hq, Hkv);
-    *out_bytes = make_layout(p, L, (int64_t)Hq * Lq, window_job(L, 1, nullptr, n_pool_kernels)).total;
+    *out_bytes = make_layout(p, L, (int64_t)Hq * Lq, window_job(L, 0, 1, nullptr, n_pool_kernels)).total;
     return ILRE_OK;
 }
 
@@ -321,7 +324,7 @@ int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, i
     if (!row_max || !row_sumexp || !out_scores) return fail(ILRE_EINVAL, "row_max, row_sumexp or out_scores is null");
     const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
     const int64_t nrows = (int64_t)Hq * Lq;
-    const Layout lay = make_layout(p, L, nrows, window_job(L, 1, nullptr, 0));
+    const Layout lay = make_layout(p, L, nrows, window_job(L, 0, 1, nullptr, 0));
     if ((rc = check_workspace(opts, lay.select))) return rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
@@ -344,13 +347,16 @@ int ilre_select(const float *scores, int64_t L, int32_t budget, const int32_t *p
     if (L < 1 || L > 0x7FFFFFFFll) return fail(ILRE_EINVAL, "L must be in [1, 2^31)");
     if (!scores || !out_idx) return fail(ILRE_EINVAL, "scores or out_idx is null");
     if ((uintptr_t)scores & 15) return fail(ILRE_EINVAL, "scores must be 16-byte aligned");
-    if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
+    if (opts->sink > L) return fail(ILRE_EINVAL, "sink must be in [0, L]");
+    if ((rc = check_kernels(L - opts->sink, budget, pool_kernels, opts->n_pool_kernels))) return rc;
     // The selection region sits at the end of the workspace whatever the scoring shape was; used
-    // alone it starts at the workspace base.
-    const ilre::SelectJob job = window_job(L, budget, pool_kernels, opts->n_pool_kernels);
+    // alone it starts at the workspace base.  Sized for the whole context, so that one workspace serves
+    // every sink size.
+    const ilre::SelectLayout sized = ilre::make_select_layout(window_job(L, 0, budget, pool_kernels, opts->n_pool_kernels));
+    if ((rc = check_workspace(opts, sized.total))) return rc;
+    const ilre::SelectJob job = window_job(L, opts->sink, budget, pool_kernels, opts->n_pool_kernels);
     const ilre::SelectLayout sel = ilre::make_select_layout(job);
-    if ((rc = check_workspace(opts, sel.total))) return rc;
-    const hipError_t e = ilre::launch_select(scores, job, out_idx, nullptr, opts->workspace, sel, (hipStream_t)opts->stream);
+    const hipError_t e = ilre::launch_select(scores + opts->sink, job, out_idx, nullptr, opts->workspace, sel, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "selection launch");
     return ILRE_OK;
 }
@@ -478,14 +484,17 @@ int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     if ((rc = check_shape(L, Lq, Hq, Hkv, d, opts->dtype))) return rc;
     if (!out_idx || !out_scores) return fail(ILRE_EINVAL, "out_idx or out_scores is null");
     if ((uintptr_t)out_scores & 15) return fail(ILRE_EINVAL, "out_scores must be 16-byte aligned");
-    if ((rc = check_kernels(L, budget, pool_kernels, opts->n_pool_kernels))) return rc;
+    if (opts->sink > L) return fail(ILRE_EINVAL, "sink must be in [0, L]");
+    if ((rc = check_kernels(L - opts->sink, budget, pool_kernels, opts->n_pool_kernels))) return rc;
     const ilre::ScorePlan p = ilre::make_score_plan(opts->dtype, L, Lq, Hq, Hkv);
-    const ilre::SelectJob job = window_job(L, budget, pool_kernels, opts->n_pool_kernels);
-    const Layout lay = make_layout(p, L, (int64_t)Hq * Lq, job);
+    // workspace sized for the whole context (what ilre_workspace_bytes reports); the selection then runs on the body
+    const Layout lay = make_layout(p, L, (int64_t)Hq * Lq, window_job(L, 0, budget, pool_kernels, opts->n_pool_kernels));
     if ((rc = check_workspace(opts, lay.total))) return rc;
     if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay))) return rc;
     unsigned char *ws = (unsigned char *)opts->workspace;
-    const hipError_t e = ilre::launch_select(out_scores, job, out_idx, nullptr, ws + lay.select, lay.sel, (hipStream_t)opts->stream);
+    const ilre::SelectJob job = window_job(L, opts->sink, budget, pool_kernels, opts->n_pool_kernels);
+    const hipError_t e = ilre::launch_select(out_scores + opts->sink, job, out_idx, nullptr, ws + lay.select,
+                                             ilre::make_select_layout(job), (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "selection launch");
     return ILRE_OK;
 }

@@ -93,7 +93,9 @@ struct SelectLayout {
     size_t cmax;      // float [ceil(L / kSelFine)]: fine-chunk maxima (pruning pre-pass)
     size_t active;    // uint32 [ceil(L / kSelFine)]: fine chunks left after pruning
     size_t cells;     // float: the max-pooled cell arrays, one per max kernel (kSelMaxAvg)
-    size_t cand;      // uint64 [n][kCandCap]
+    size_t picked;    // uint32 [ILRE_MAX_BUDGET] the allocated tokens in the order they were taken, then their count
+    size_t seed;      // kSelWindowMax: uint32 rank[kCandCap], int32 dom_left[kCandCap], int32 dom_right[kCandCap]
+    size_t cand;      // uint64 [n][kCandCap]; kSelWindowMax: [1 + n][kCandCap], list 0 the seeds, then a token list per kernel size
     size_t tie;       // uint64: per combination two ping-pong lists of boundary elements, each as long as its source
     size_t total;
 };

@@ -25,9 +25,28 @@
 //                compacted) to what is needed -- in the window-max form only while it is longer than
 //                kSelSmall, extra candidates rank last and are harmless; in the printed form to
 //                exactly K_m elements -- and joins the candidates
-//   allocate     one workgroup walks the combinations in order: the tokens of the candidate elements
-//                that are not yet allocated (LDS hash set), exact radix select of the B_j largest
-//                among them in registers, then the allocated set sorted ascending behind the sink part.
+//   allocate_ranked   one workgroup walks the combinations in order over their rank-ordered token lists: a
+//                token already allocated (LDS hash set) is skipped, the first B_j others are taken
+//   emit_sorted  the allocated set in ascending order behind the sink part (each token counts the
+//                tokens below it)
+//
+// The window-max form does not pool while it scans.  With B' = min(B, L), only the B' best raw scores by
+// (score descending, token ascending), the "seeds", can decide anything: the K_j-th largest pooled value
+// of any kernel size is at least the B'-th largest raw score (pooling only raises values and K_j <= B'),
+// so every candidate token has a seed inside its window, and a seed that B' others outrank owns no token
+// of any candidate prefix.  Hence:
+//
+//   sel_init, pool_hist<1>, pool_hist<2>, collect, refine    as above, for ONE combination with window 1:
+//                the B' best raw scores (plus, harmlessly, up to kSelSmall more that share the 22-bit
+//                prefix of the last one)
+//   seed_rank    per seed: its rank among the seeds (counting, 16 lanes a seed) and the nearest seed that
+//                outranks it on either side (a scan of the raw scores around it: whatever outranks a seed
+//                is a seed)
+//   seed_lists   one workgroup per kernel size: seed u owns the tokens whose window holds u and no seed
+//                that outranks u, an interval [max(u-r, a+r+1), min(u+r, b-r-1)]; their pooled value is
+//                u's score.  Seeds in rank order, each interval ascending, is the kernel size's ranked
+//                token list; its first K_j tokens are written out
+//   allocate_ranked   the walk over those lists (shared with the printed form)
 //
 // Long contexts in the window-max form (L >= 4M and >= 1024 tokens per budgeted token) start with a
 // pruning pre-pass: the maximum of every fine chunk (one streaming read of the scores), the 22-bit
@@ -45,14 +64,13 @@
 namespace ilre {
 namespace {
 
-constexpr int kThreads = 1024;                    // refine, allocate: one large workgroup
+constexpr int kThreads = 1024;                    // refine, seed_lists: one large workgroup
 constexpr int kPoolThreads = 256;                 // pooling passes: four wavefronts, one fine chunk each
 constexpr int kPoolWaves = kPoolThreads / 64;
 constexpr int kPerThread = kSelFine / 64;         // 4 tokens per lane
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kHashSlots = 16384;                 // >= 2 * ILRE_MAX_BUDGET
 constexpr int kKeysPerThread = kCandCap / kThreads;
-constexpr int kBuckets = 4096;                       // final counting sort (3 * kBuckets <= kHashSlots)
 
 // Per-combination description, host -> sel_init (by value), which copies it into the control blocks.
 struct SelParams {
@@ -111,28 +129,6 @@ __device__ __forceinline__ uint32_t wave_total(uint32_t scanned)  // lane 63 of 
 {
     return (uint32_t)__builtin_amdgcn_readlane((int)scanned, 63);
 }
-template <bool IS_AND>
-__device__ __forceinline__ uint32_t wave_bits32(uint32_t x)  // AND or OR over the 64 lanes, in every lane
-{
-    const uint32_t id = IS_AND ? 0xFFFFFFFFu : 0u;
-#define ILRE_STEP(ctrl, rows)                                      \
-    {                                                              \
-        const uint32_t y = (uint32_t)ILRE_DPP(id, x, ctrl, rows);  \
-        x = IS_AND ? (x & y) : (x | y);                            \
-    }
-    ILRE_STEP(0x111, 0xF) ILRE_STEP(0x112, 0xF) ILRE_STEP(0x114, 0xF) ILRE_STEP(0x118, 0xF) ILRE_STEP(0x142, 0xA) ILRE_STEP(0x143, 0xC)
-#undef ILRE_STEP
-    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
-}
-__device__ __forceinline__ uint64_t wave_and64(uint64_t x)
-{
-    return ((uint64_t)wave_bits32<true>((uint32_t)(x >> 32)) << 32) | wave_bits32<true>((uint32_t)x);
-}
-__device__ __forceinline__ uint64_t wave_or64(uint64_t x)
-{
-    return ((uint64_t)wave_bits32<false>((uint32_t)(x >> 32)) << 32) | wave_bits32<false>((uint32_t)x);
-}
-
 // Inclusive prefix sum over the THREADS threads of the block; wsum is THREADS / 64 words of LDS
 // scratch.  Every thread also receives the block total.  Contains two barriers.
 template <int THREADS>
@@ -236,6 +232,16 @@ __device__ __forceinline__ size_t pool_lds_floats(int before, int after) { retur
 __device__ __forceinline__ void pooled_wave(const Pooling &pl, int64_t fc, float *b0, float *b1, float (&out)[kPerThread])
 {
     const int lane = threadIdx.x & 63;
+    if (pl.op == kSelWindowMax && pl.before + pl.after == 0) {
+        // window 1 (the seed pass of the window-max form): the elements themselves, no trip through LDS
+        // (callers ignore the lanes past the end of the array)
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int64_t e = fc * kSelFine + lane + k * 64;
+            out[k] = pl.src[e < pl.len ? e : pl.len - 1];
+        }
+        return;
+    }
     const int len = kSelFine + pl.before + pl.after;
     const int64_t first = fc * kSelFine - pl.before;
     const float pad = pl.op == kSelMaxAvg ? 0.0f : -INFINITY;
@@ -465,18 +471,19 @@ __global__ __launch_bounds__(kPoolThreads) void chunk_max(const float *scores, i
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t stride = gridDim.x * kPoolWaves * 4;
+    const bool aligned = ((size_t)scores & 15) == 0;  // a sink part may shift the body off the 16-byte grid
     for (uint32_t c0 = (blockIdx.x * kPoolWaves + wave) * 4; c0 < nfine; c0 += stride) {
         float4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int64_t tok = (int64_t)(c0 + u) * kSelFine + lane * 4;
-            if (tok + 3 < L) {
+            if (aligned && tok + 3 < L) {
                 v[u] = *(const float4 *)(scores + tok);
             } else {
                 v[u].x = tok + 0 < L ? scores[tok + 0] : -INFINITY;
                 v[u].y = tok + 1 < L ? scores[tok + 1] : -INFINITY;
                 v[u].z = tok + 2 < L ? scores[tok + 2] : -INFINITY;
-                v[u].w = -INFINITY;
+                v[u].w = tok + 3 < L ? scores[tok + 3] : -INFINITY;
             }
         }
 #pragma unroll
@@ -641,243 +648,35 @@ __device__ __forceinline__ void mark_allocated(uint32_t *table, uint32_t token)
     }
 }
 
-// Last step of both allocation kernels: the sink indices, then the nsel allocated tokens in ascending
-// order (counting sort on the high bits into kBuckets buckets, then each token's rank inside its bucket
-// by counting the smaller ones: deterministic whatever order the tokens arrived in), then -1 up to
-// sink + n_out.  table (the hash set, no longer needed) and the second half of sel are scratch.
-template <int THREADS>
-__device__ __forceinline__ void emit_ascending(uint32_t *table, uint32_t *sel, uint32_t *wsum, uint32_t nsel, int n_out,
-                                               int sink, int bucket_shift, int32_t *out_idx, int32_t *out_count)
+// Last step of the allocation: the sink indices, then the nsel allocated tokens in ascending order, then -1
+// up to sink + n_out.  The walk leaves the tokens in the order it took them; here every token counts the
+// tokens below it (16 lanes a token, the list staged in LDS), which is its place in the output whatever
+// order they arrived in and however they cluster.
+constexpr int kEmitThreads = 512;  // 32 tokens a workgroup
+__global__ __launch_bounds__(kEmitThreads) void emit_sorted(const uint32_t *picked, const uint32_t *picked_n, int n_out, int sink,
+                                                            int32_t *out_idx, int32_t *out_count)
 {
-    uint32_t *cnt = table;                  // the hash set is no longer needed
-    uint32_t *start = table + kBuckets;
-    uint32_t *fill = table + 2 * kBuckets;
-    uint32_t *grp = sel + ILRE_MAX_BUDGET;
-    for (int i = threadIdx.x; i < kBuckets; i += THREADS) {
-        cnt[i] = 0;
-        fill[i] = 0;
-    }
+    __shared__ uint32_t all[ILRE_MAX_BUDGET];
+    const uint32_t nsel = *picked_n;
+    const uint32_t gtid = blockIdx.x * kEmitThreads + threadIdx.x, gsize = gridDim.x * kEmitThreads;
+    for (uint32_t i = gtid; i < (uint32_t)sink; i += gsize) out_idx[i] = (int32_t)i;
+    for (uint32_t i = nsel + gtid; i < (uint32_t)n_out; i += gsize) out_idx[sink + i] = -1;
+    if (gtid == 0 && out_count) *out_count = sink + (int32_t)nsel;
+    if (blockIdx.x * (kEmitThreads / 16) >= nsel) return;  // uniform
+    for (uint32_t i = threadIdx.x; i < nsel; i += kEmitThreads) all[i] = picked[i];
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < nsel; i += THREADS) atomicAdd(&cnt[sel[i] >> bucket_shift], 1u);
-    __syncthreads();
-    {
-        constexpr int BPT = kBuckets / THREADS;
-        uint32_t own[BPT], sum = 0;
-#pragma unroll
-        for (int k = 0; k < BPT; ++k) {
-            own[k] = cnt[threadIdx.x * BPT + k];
-            sum += own[k];
-        }
-        uint32_t total;
-        uint32_t run = block_scan_inclusive<THREADS>(sum, wsum, total) - sum;
-#pragma unroll
-        for (int k = 0; k < BPT; ++k) {
-            start[threadIdx.x * BPT + k] = run;
-            run += own[k];
-        }
-    }
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < nsel; i += THREADS) {
-        const uint32_t t = sel[i], bkt = t >> bucket_shift;
-        grp[start[bkt] + atomicAdd(&fill[bkt], 1u)] = t;
-    }
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < nsel; i += THREADS) {
-        const uint32_t t = grp[i], bkt = t >> bucket_shift;
-        const uint32_t s0 = start[bkt], s1 = s0 + cnt[bkt];
-        uint32_t rank = s0;
-        for (uint32_t q = s0; q < s1; ++q) rank += grp[q] < t ? 1u : 0u;
-        out_idx[sink + rank] = (int32_t)(t + sink);
-    }
-    for (int i = threadIdx.x; i < sink; i += THREADS) out_idx[i] = i;
-    for (int i = nsel + threadIdx.x; i < n_out; i += THREADS) out_idx[sink + i] = -1;
-    if (threadIdx.x == 0 && out_count) *out_count = sink + (int32_t)nsel;
-}
-
-// Algorithm 1's walk, window-max form: kernels in the order given; from kernel j's candidates the B_j
-// largest keys whose tokens are not yet allocated; then the output.
-__global__ __launch_bounds__(kThreads) void allocate(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out, int sink,
-                                                     int bucket_shift, int32_t *out_idx, int32_t *out_count)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t *table = (uint32_t *)smem;  // kHashSlots
-    uint32_t *sel = table + kHashSlots;  // ILRE_MAX_BUDGET tokens, then as many again for the final sort
-    __shared__ uint32_t wsum[kThreads / 64];
-    __shared__ uint64_t red[2][3][kThreads / 64];  // per-wave (count, and, or), two generations
-    __shared__ uint32_t h[3][256];                 // digit histograms, three generations
-    __shared__ uint32_t nsel_ctr;
-    constexpr int kDirect = 128;                   // a threshold bin this small is ranked directly
-    __shared__ uint64_t small[kDirect];
-    __shared__ uint64_t small_thr;
-    __shared__ uint32_t small_n;
-
-    for (int i = threadIdx.x; i < kHashSlots; i += kThreads) table[i] = kEmpty;
-    if (threadIdx.x < 256) h[0][threadIdx.x] = h[1][threadIdx.x] = h[2][threadIdx.x] = 0;
-    if (threadIdx.x == 0) {
-        nsel_ctr = 0;
-        small_n = 0;
-    }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-    uint64_t key[kKeysPerThread];
-    auto fetch = [&](int j, uint64_t(&dst)[kKeysPerThread]) {
-        const uint32_t cn = ctrl[j].total_n;
-        const uint64_t *cand_j = cand + (size_t)j * kCandCap;
-#pragma unroll
-        for (int k = 0; k < kKeysPerThread; ++k) {
-            const uint32_t i = threadIdx.x + k * kThreads;  // < kCandCap: always inside the list's storage
-            dst[k] = cand_j[i];
-        }
-#pragma unroll
-        for (int k = 0; k < kKeysPerThread; ++k)
-            if (threadIdx.x + k * kThreads >= cn) dst[k] = 0;  // 0 is below every real key
-    };
-    __syncthreads();
-
-    uint32_t nsel = 0;
-    int gen = 0, hgen = 0;  // generations of red[] and h[], advanced uniformly
-    for (int j = 0; j < n; ++j) {
-        uint32_t share = ctrl[j].share;
-        if ((uint32_t)n_out - nsel < share) share = (uint32_t)n_out - nsel;
-        if (share == 0) continue;  // uniform
-        fetch(j, key);
-
-        // which of this thread's candidates are still free
-        uint32_t free_mask = 0, nfree = 0;
-        uint64_t vand = ~0ull, vor = 0;
-#pragma unroll
-        for (int k = 0; k < kKeysPerThread; ++k) {
-            if (key[k] == 0) continue;
-            if (!is_allocated(table, key_token(key[k]))) {
-                free_mask |= 1u << k;
-                ++nfree;
-                vand &= key[k];
-                vor |= key[k];
-            }
-        }
-        // block-wide count, AND and OR of the free keys: one exchange through LDS
-        const uint64_t c64 = wave_total(wave_scan_add(nfree));
-        vand = wave_and64(vand);
-        vor = wave_or64(vor);
-        if (lane == 0) {
-            red[gen][0][wave] = c64;
-            red[gen][1][wave] = vand;
-            red[gen][2][wave] = vor;
-        }
-        __syncthreads();
-        uint64_t total_free = 0, all_and = ~0ull, all_or = 0;
-#pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) {
-            total_free += red[gen][0][w];
-            all_and &= red[gen][1][w];
-            all_or |= red[gen][2][w];
-        }
-        gen ^= 1;
-        const uint32_t take = share < (uint32_t)total_free ? share : (uint32_t)total_free;
-        if (take == 0) continue;  // uniform
-
-        // threshold: the take-th largest free key.  Radix select, 8 bits a pass, from the highest bit
-        // in which the free keys differ; keys are distinct, so it ends with exactly `take` keys at or
-        // above the threshold.  One barrier per pass: every wavefront locates the digit itself, and the
-        // histogram two generations back is cleared while the current one fills.
-        uint64_t thr = 0;
-        if (take < (uint32_t)total_free) {
-            const uint64_t diff = all_and ^ all_or;  // != 0: at least two distinct keys
-            int shift = 63 - __clzll((long long)diff) - 7;
-            if (shift < 0) shift = 0;
-            uint64_t pmask = shift + 8 >= 64 ? 0ull : ~0ull << (shift + 8);
-            uint64_t prefix = all_and & pmask;
-            uint32_t need = take;
-            bool direct = false;
-            while (true) {
-                uint32_t *hc = h[hgen];
-                if (threadIdx.x < 256) h[(hgen + 1) % 3][threadIdx.x] = 0;
-#pragma unroll
-                for (int k = 0; k < kKeysPerThread; ++k)
-                    if (((free_mask >> k) & 1u) && (key[k] & pmask) == prefix) atomicAdd(&hc[(key[k] >> shift) & 255u], 1u);
-                __syncthreads();
-                // lane l owns digits 255-4l .. 252-4l (descending)
-                uint32_t own[4], sum = 0;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    own[k] = hc[255 - (lane * 4 + k)];
-                    sum += own[k];
-                }
-                const uint32_t incl = wave_scan_add(sum);
-                uint32_t above = incl - sum;
-                uint32_t found = 0;  // digit | inside << 8 (inside <= kCandCap) ; above kept separately
-                uint32_t found_above = 0;
-                if (above < need && need <= incl) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        if (above < need && need <= above + own[k]) {
-                            found = (255u - (lane * 4 + k)) | (own[k] << 8) | 0x80000000u;
-                            found_above = above;
-                        }
-                        above += own[k];
-                    }
-                }
-                const uint64_t who = __ballot(found != 0);
-                const int src_lane = __ffsll((unsigned long long)who) - 1;
-                found = (uint32_t)__builtin_amdgcn_readlane((int)found, src_lane);
-                found_above = (uint32_t)__builtin_amdgcn_readlane((int)found_above, src_lane);
-                const uint32_t digit = found & 255u, inside = (found >> 8) & 0x7FFFFFu;
-                hgen = (hgen + 1) % 3;
-                prefix |= (uint64_t)digit << shift;
-                pmask |= 255ull << shift;
-                need -= found_above;
-                if (need == inside || shift == 0) break;  // the whole digit bin is taken
-                if (inside <= (uint32_t)kDirect) {
-                    direct = true;  // few keys left in the bin: rank them against each other instead
-                    break;
-                }
-                shift = shift >= 8 ? shift - 8 : 0;  // the last digit may overlap the one before: harmless
-            }
-            thr = prefix;
-            if (direct) {  // uniform
-                // The bin's keys go to a list; key i is the threshold if exactly need - 1 of the others
-                // are larger (keys are distinct).  Two barriers instead of up to seven more passes when
-                // the cut falls inside a plateau of equal pooled scores, where only index bits differ.
-#pragma unroll
-                for (int k = 0; k < kKeysPerThread; ++k)
-                    if (((free_mask >> k) & 1u) && (key[k] & pmask) == prefix) small[atomicAdd(&small_n, 1u)] = key[k];
-                __syncthreads();
-                const uint32_t ns = small_n;  // == inside
-                if (threadIdx.x < ns) {
-                    const uint64_t mine = small[threadIdx.x];
-                    uint32_t larger = 0;
-                    for (uint32_t i = 0; i < ns; ++i) larger += small[i] > mine ? 1u : 0u;
-                    if (larger == need - 1) small_thr = mine;
-                }
-                __syncthreads();
-                thr = small_thr;
-                if (threadIdx.x == 0) small_n = 0;  // next use lies behind the barrier that ends this kernel size
-            }
-        }
-
-        // take every free key >= thr: one slot reservation per wavefront
-        uint32_t take_mask = 0;
-#pragma unroll
-        for (int k = 0; k < kKeysPerThread; ++k)
-            if (((free_mask >> k) & 1u) && key[k] >= thr) take_mask |= 1u << k;
-        const uint32_t mine = (uint32_t)__popc(take_mask);
-        const uint32_t incl = wave_scan_add(mine);
-        uint32_t base = 0;
-        if (lane == 63 && incl) base = atomicAdd(&nsel_ctr, incl);
-        uint32_t pos = (uint32_t)__builtin_amdgcn_readlane((int)base, 63) + incl - mine;
-#pragma unroll
-        for (int k = 0; k < kKeysPerThread; ++k) {
-            if ((take_mask >> k) & 1u) {
-                const uint32_t token = key_token(key[k]);
-                sel[pos++] = token;
-                mark_allocated(table, token);
-            }
-        }
-        __syncthreads();
-        nsel = nsel_ctr;
-    }
-    __syncthreads();
-    emit_ascending<kThreads>(table, sel, wsum, nsel, n_out, sink, bucket_shift, out_idx, out_count);
+    const uint32_t i = blockIdx.x * (kEmitThreads / 16) + (threadIdx.x >> 4);
+    const int sub = threadIdx.x & 15;
+    if (i >= nsel) return;  // whole 16-lane groups leave together, no barrier follows
+    const uint32_t t = all[i];
+    uint32_t below = 0;
+#pragma unroll 8
+    for (uint32_t v = sub; v < nsel; v += 16) below += all[v] < t ? 1u : 0u;
+    below += (uint32_t)ILRE_DPP(0, below, 0x111, 0xF);
+    below += (uint32_t)ILRE_DPP(0, below, 0x112, 0xF);
+    below += (uint32_t)ILRE_DPP(0, below, 0x114, 0xF);
+    below += (uint32_t)ILRE_DPP(0, below, 0x118, 0xF);  // lane 15 of the row holds the total
+    if (sub == 15) out_idx[sink + below] = (int32_t)(t + (uint32_t)sink);
 }
 
 // LDS writes of this wavefront done, then the workgroup barrier; global loads in flight stay in flight.
@@ -896,13 +695,11 @@ constexpr int kRankPer = kRankGroups * kRankG;                                  
 static_assert(kRankPer <= 64, "free tokens of a lane are kept in a 64-bit mask");
 
 __global__ __launch_bounds__(kRankThreads) void allocate_ranked(const SelCtrl *ctrl, const uint64_t *cand, int n, int n_out,
-                                                                int sink, int bucket_shift, int32_t *out_idx,
-                                                                int32_t *out_count)
+                                                                uint32_t *picked, uint32_t *picked_n)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t *table = (uint32_t *)smem;  // kHashSlots
-    uint32_t *sel = table + kHashSlots;  // ILRE_MAX_BUDGET tokens, then as many again for the final sort
-    __shared__ uint32_t wsum[kRankWaves];
+    uint32_t *sel = table + kHashSlots;  // ILRE_MAX_BUDGET tokens
     __shared__ uint32_t wfree[2][kRankWaves];  // free tokens per wavefront, two generations
     __shared__ uint32_t c_share[ILRE_MAX_POOL_KERNELS], c_tokens[ILRE_MAX_POOL_KERNELS];
 
@@ -1029,7 +826,130 @@ __global__ __launch_bounds__(kRankThreads) void allocate_ranked(const SelCtrl *c
         lds_barrier();  // the set is complete before the next combination probes it
     }
     __syncthreads();
-    emit_ascending<kRankThreads>(table, sel, wsum, nsel, n_out, sink, bucket_shift, out_idx, out_count);
+    // the allocated tokens, in the order they were taken, for emit_sorted
+    for (uint32_t i = threadIdx.x; i < nsel; i += kRankThreads) picked[i] = sel[i];
+    if (threadIdx.x == 0) *picked_n = nsel;
+}
+
+
+// ---------------------------------------------------------------- window-max form: seeds
+
+// Per seed u (one of the ns best raw scores, keys distinct): rank[u] = number of seeds with a larger key,
+// and the nearest token on either side, within `reach` tokens, whose key is larger (-1 / -1 if none; such a
+// token is itself a seed, the seeds being the best keys).  16 lanes share a seed: they split the other
+// seeds for the count and the neighbourhood for the scan.
+constexpr int kSeedRankThreads = 512;  // 32 seeds a workgroup
+__global__ __launch_bounds__(kSeedRankThreads) void seed_rank(const float *scores, int64_t L, const SelCtrl *sc, const uint64_t *seeds,
+                                                              int reach, uint32_t *rank, int32_t *dom_left, int32_t *dom_right)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint64_t *all = (uint64_t *)smem;  // every seed's key, staged once per workgroup (kCandCap at most)
+    const uint32_t ns = sc->total_n;
+    if (blockIdx.x * (kSeedRankThreads / 16) >= ns) return;  // uniform
+    // (the seeds were written by earlier kernels: plain loads, all in flight together)
+    for (uint32_t i = threadIdx.x; i < ns; i += kSeedRankThreads) all[i] = seeds[i];
+    __syncthreads();
+    const uint32_t u = blockIdx.x * (kSeedRankThreads / 16) + (threadIdx.x >> 4);
+    const int sub = threadIdx.x & 15;
+    if (u >= ns) return;  // whole 16-lane groups leave together, no barrier follows
+    const uint64_t key = all[u];
+    uint32_t cnt = 0;
+#pragma unroll 8
+    for (uint32_t v = sub; v < ns; v += 16) cnt += all[v] > key ? 1u : 0u;
+    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x111, 0xF);
+    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x112, 0xF);
+    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x114, 0xF);
+    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x118, 0xF);  // lane 15 of the row holds the total
+    const int64_t pos = (int64_t)key_token(key);
+    // nearest outranking token: distance d = 1 .. reach, 16 distances a round, both sides at once
+    int32_t left = -1, right = -1;
+    for (int d0 = 1; d0 <= reach; d0 += 16) {
+        const int d = d0 + sub;
+        const int64_t pl = pos - d, pr = pos + d;
+        const bool hit_l = d <= reach && pl >= 0 && make_key(scores[pl < 0 ? 0 : pl], (uint32_t)(pl < 0 ? 0 : pl)) > key;
+        const bool hit_r = d <= reach && pr < L && make_key(scores[pr < L ? pr : L - 1], (uint32_t)(pr < L ? pr : L - 1)) > key;
+        // lowest lane of this 16-lane group with a hit = smallest distance
+        const uint64_t bl = __ballot(left < 0 && hit_l), br = __ballot(right < 0 && hit_r);
+        const int shift = (threadIdx.x & 63) & ~15;
+        const uint32_t ml = (uint32_t)(bl >> shift) & 0xFFFFu, mr = (uint32_t)(br >> shift) & 0xFFFFu;
+        if (left < 0 && ml) left = (int32_t)(pos - (d0 + __ffs((int)ml) - 1));
+        if (right < 0 && mr) right = (int32_t)(pos + (d0 + __ffs((int)mr) - 1));
+        if (left >= 0 && right >= 0) break;  // uniform within the group; ballots are wave-wide but only read per group
+    }
+    if (sub == 15) {
+        rank[u] = cnt;
+        dom_left[u] = left;
+        dom_right[u] = right;
+    }
+}
+
+// One workgroup per kernel size j: the first K_j tokens of its ranked token list (uint32, in the storage of
+// cand list 1 + j) and its control block for the walk.  LDS: lo[kCandCap] and the running token counts
+// pre[kCandCap], both indexed by seed rank.
+struct SeedParams {
+    int n;
+    uint32_t radius[ILRE_MAX_POOL_KERNELS], share[ILRE_MAX_POOL_KERNELS], want[ILRE_MAX_POOL_KERNELS];
+};
+__global__ __launch_bounds__(kThreads) void seed_lists(const SeedParams prm, int64_t L, const SelCtrl *sc, const uint64_t *seeds,
+                                                       const uint32_t *rank, const int32_t *dom_left, const int32_t *dom_right,
+                                                       SelCtrl *kctrl, uint64_t *cand)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    int32_t *lo = (int32_t *)smem;
+    uint32_t *pre = (uint32_t *)(lo + kCandCap);
+    __shared__ uint32_t wsum[kThreads / 64];
+    const int j = blockIdx.x;
+    const uint32_t ns = sc->total_n;
+    const int64_t r = prm.radius[j];
+    for (uint32_t u = threadIdx.x; u < ns; u += kThreads) {
+        const int64_t pos = (int64_t)key_token(seeds[u]);
+        const int64_t a = dom_left[u], b = dom_right[u];
+        int64_t first = pos - r, last = pos + r;
+        if (first < 0) first = 0;
+        if (last > L - 1) last = L - 1;
+        if (a >= 0 && a + r + 1 > first) first = a + r + 1;
+        if (b >= 0 && b - r - 1 < last) last = b - r - 1;
+        const uint32_t rk = rank[u];
+        lo[rk] = (int32_t)first;
+        pre[rk] = last >= first ? (uint32_t)(last - first + 1) : 0u;
+    }
+    __syncthreads();
+    // inclusive running sum of the interval lengths in rank order: thread t owns ranks t*kKeysPerThread ..
+    uint32_t own[kKeysPerThread], sum = 0;
+#pragma unroll
+    for (int k = 0; k < kKeysPerThread; ++k) {
+        const uint32_t i = threadIdx.x * kKeysPerThread + k;
+        own[k] = i < ns ? pre[i] : 0u;
+        sum += own[k];
+    }
+    uint32_t total;
+    uint32_t run = block_scan_inclusive<kThreads>(sum, wsum, total) - sum;
+#pragma unroll
+    for (int k = 0; k < kKeysPerThread; ++k) {
+        const uint32_t i = threadIdx.x * kKeysPerThread + k;
+        run += own[k];
+        if (i < ns) pre[i] = run;
+    }
+    __syncthreads();
+    const uint32_t want = prm.want[j] < total ? prm.want[j] : total;
+    uint32_t *tokens = (uint32_t *)(cand + (size_t)(1 + j) * kCandCap);
+    for (uint32_t i = threadIdx.x; i < want; i += kThreads) {
+        // the seed whose interval holds ranked token i: the first rank with pre[rank] > i
+        uint32_t lo_r = 0, hi_r = ns - 1;
+        while (lo_r < hi_r) {
+            const uint32_t mid = (lo_r + hi_r) >> 1;
+            if (pre[mid] > i) hi_r = mid; else lo_r = mid + 1;
+        }
+        const uint32_t before = lo_r ? pre[lo_r - 1] : 0u;
+        tokens[i] = (uint32_t)lo[lo_r] + (i - before);
+    }
+    if (threadIdx.x == 0) {
+        SelCtrl c{};
+        c.share = prm.share[j];
+        c.total_n = want;
+        c.cell = 1;
+        kctrl[j] = c;
+    }
 }
 
 // Last line of Algorithm 1: the input IDs of the allocated tokens, C[I].  Unused index slots (-1) give -1.
@@ -1067,34 +987,174 @@ SelectLayout make_select_layout(const SelectJob &job)
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     SelectLayout lay{};
     const int n = job.combos() > 0 ? job.combos() : 1;
+    const bool window = job.mode == kSelWindowMax;
+    // histogram passes run per combination in the printed form, for the single seed combination in the
+    // window-max form; one more set belongs to the pruning pre-pass
+    const int nh = window ? 1 : n;
     const size_t nfine = (size_t)((job.L + kSelFine - 1) / kSelFine);
     size_t off = 0;
     lay.hist = off;
-    off = up(off + 2 * (size_t)(n + 1) * kSelBins * sizeof(uint32_t));  // + the pre-pass's own pair
+    off = up(off + 2 * (size_t)(nh + 1) * kSelBins * sizeof(uint32_t));
     lay.ctrl = off;
-    off = up(off + (size_t)(n + 1) * sizeof(SelCtrl));
+    off = up(off + (size_t)(nh + 1 + (window ? n : 0)) * sizeof(SelCtrl));
     lay.done = off;
-    off = up(off + 2 * (size_t)(n + 1) * sizeof(uint32_t));
+    off = up(off + 2 * (size_t)(nh + 1) * sizeof(uint32_t));
     lay.cmax = off;
     off = up(off + nfine * sizeof(float));
     lay.active = off;
     off = up(off + nfine * sizeof(uint32_t));
     lay.cells = off;
     size_t ncell = 0, ntie = 0;
-    if (job.mode == kSelMaxAvg) {
+    if (!window) {
         for (int i = 0; i < job.n_max; ++i) ncell += (size_t)(job.L / job.max_kernels[i]);
         ntie = 2 * ncell * (size_t)job.n_avg;
     } else {
-        ntie = 2 * (size_t)job.L * (size_t)n;
+        ntie = 2 * (size_t)job.L;
     }
     off = up(off + ncell * sizeof(float));
+    lay.picked = off;
+    off = up(off + ((size_t)ILRE_MAX_BUDGET + 64) * sizeof(uint32_t));
+    lay.seed = off;
+    off = up(off + (window ? 3 * (size_t)kCandCap * sizeof(uint32_t) : 0));
     lay.cand = off;
-    off = up(off + (size_t)n * kCandCap * sizeof(uint64_t));
+    off = up(off + (size_t)(window ? n + 1 : n) * kCandCap * sizeof(uint64_t));
     lay.tie = off;
     off = up(off + ntie * sizeof(uint64_t));
     lay.total = off;
     return lay;
 }
+
+namespace {
+
+// Dynamic LDS ceilings of the selection kernels: the same constants on every call, set once per process
+// and device-independent.
+hipError_t set_select_attributes()
+{
+    static hipError_t status = [] {
+        constexpr int kAllocLds = kHashSlots * (int)sizeof(uint32_t) + ILRE_MAX_BUDGET * (int)sizeof(uint32_t);
+        constexpr int kPoolLdsMax = kPoolWaves * 2 * (kSelFine + 2 * (ILRE_MAX_AVG_KERNEL > ILRE_MAX_POOL_KERNEL ? ILRE_MAX_AVG_KERNEL : ILRE_MAX_POOL_KERNEL)) * (int)sizeof(float);
+        constexpr int kSortLdsMax = 16384 * (int)sizeof(uint64_t);  // >= ILRE_MAX_BUDGET + 1 keys, padded to a power of two
+        constexpr int kSeedLds = 2 * kCandCap * (int)sizeof(uint32_t);
+        constexpr int kSeedRankLds = kCandCap * (int)sizeof(uint64_t);
+        hipError_t e;
+        if ((e = hipFuncSetAttribute((const void *)allocate_ranked, hipFuncAttributeMaxDynamicSharedMemorySize, kAllocLds)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)pool_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)refine, hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsMax)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)seed_lists, hipFuncAttributeMaxDynamicSharedMemorySize, kSeedLds)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)seed_rank, hipFuncAttributeMaxDynamicSharedMemorySize, kSeedRankLds)) != hipSuccess) return e;
+        return hipSuccess;
+    }();
+    return status;
+}
+
+uint32_t pool_blocks(uint32_t entries, uint32_t cap)
+{
+    const uint32_t want = (entries + kPoolWaves - 1) / kPoolWaves;
+    return want < cap ? (want ? want : 1u) : cap;
+}
+uint32_t clamp_u32(uint32_t x, uint32_t lo, uint32_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+// Workgroups per combination in the pooling passes; beyond the cap the wavefronts loop over the entries.
+// A histogram workgroup carries fixed work (clearing and flushing 2048 bins, one atomic per hot bin on a
+// handful of addresses, about 13 ns each and serialised, the completion counter), so those passes aim at
+// about one resident round of workgroups over all combinations.
+constexpr uint32_t kHistGrid = 2560, kCollectGrid = 8192;
+
+// Window-max form: the seeds (best raw scores), their ranks and neighbours, one ranked token list per
+// kernel size, the walk.
+hipError_t launch_select_window(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
+                                unsigned char *ws, const SelectLayout &lay, hipStream_t s)
+{
+    const int64_t L = job.L;
+    const int n = job.combos();
+    const int n_out = (int)(job.budget < L ? job.budget : L);
+    uint32_t *hist = (uint32_t *)(ws + lay.hist);
+    SelCtrl *ctrl = (SelCtrl *)(ws + lay.ctrl);  // [0] the seed combination, [1] the pruning pre-pass, [2 ..] the kernel sizes
+    uint32_t *done = (uint32_t *)(ws + lay.done);
+    uint64_t *cand = (uint64_t *)(ws + lay.cand);  // list 0: the seeds' keys; list 1 + j: kernel size j's ranked tokens
+    uint64_t *tie = (uint64_t *)(ws + lay.tie);
+    uint32_t *rank = (uint32_t *)(ws + lay.seed);
+    int32_t *dom_left = (int32_t *)(rank + kCandCap), *dom_right = dom_left + kCandCap;
+    const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
+    uint32_t *picked = (uint32_t *)(ws + lay.picked), *picked_n = picked + ILRE_MAX_BUDGET;
+    const dim3 emit_grid((unsigned)((n_out + kEmitThreads / 16 - 1) / (kEmitThreads / 16)) + 1u);
+
+    // the seed combination: window 1 on the scores, the n_out best wanted
+    SelParams prm{};
+    prm.n = 1;
+    prm.op = (uint32_t)kSelWindowMax;
+    prm.exact = 0;
+    prm.share[0] = (uint32_t)n_out;
+    prm.want[0] = (uint32_t)n_out;
+    prm.len[0] = (uint32_t)L;
+    prm.cell[0] = 1;
+    // B_c: floor(B / n), the first B mod n kernel sizes one more.  K_j: what the earlier shares could have
+    // taken plus the own share.
+    SeedParams sp{};
+    sp.n = n;
+    const int base = job.budget / n, rem = job.budget % n;
+    int64_t before = 0;
+    int r_max = 0;
+    for (int j = 0; j < n; ++j) {
+        const int share = base + (j < rem ? 1 : 0);
+        const int r = (job.max_kernels[j] - 1) / 2;
+        const int64_t want = before + share < n_out ? before + share : n_out;
+        sp.radius[j] = (uint32_t)r;
+        sp.share[j] = (uint32_t)share;
+        sp.want[j] = (uint32_t)want;
+        before += share;
+        if (r > r_max) r_max = r;
+    }
+
+    const uint32_t nfine = (uint32_t)((L + kSelFine - 1) / kSelFine);
+    const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)kSelFine * sizeof(float);
+    Entries ent{nullptr, nullptr};
+    uint32_t entries = nfine;
+    if ((int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384) {
+        // Long contexts: only fine chunks whose maximum reaches the n_out-th largest chunk maximum (up to its
+        // 22-bit prefix) can hold one of the n_out best scores; visit only those.
+        float *cm = (float *)(ws + lay.cmax);
+        uint32_t *active = (uint32_t *)(ws + lay.active);
+        uint32_t *phist = hist + 2 * (size_t)kSelBins;
+        SelCtrl *pctrl = ctrl + 1;
+        uint32_t *pdone = done + 2;
+        SelParams pp{};
+        pp.n = 1;
+        pp.len[0] = nfine;
+        pp.cell[0] = 1;
+        pp.want[0] = (uint32_t)n_out;
+        const uint32_t nfine2 = (nfine + kSelFine - 1) / kSelFine;
+        const Entries all{nullptr, nullptr};
+        hipLaunchKernelGGL(chunk_max, dim3(2048), dim3(kPoolThreads), 0, s, scores, L, nfine, cm);
+        hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, pp, phist, pctrl, pdone);
+        hipLaunchKernelGGL(pool_hist<1>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
+        hipLaunchKernelGGL(pool_hist<2>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
+        hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, cm, nfine, 0, pctrl, active);
+        ent = Entries{active, &pctrl->cand_n};
+        // with a list the entry count is only known on the device: size the grid for the worst case the
+        // pruning rule is meant for (a few times the budget) and let the wavefronts loop
+        entries = 4u * (uint32_t)n_out + 1024u;
+    }
+    const uint32_t hblocks = pool_blocks(entries, 256u), cblocks = pool_blocks(entries, 1024u);
+    hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, prm, hist, ctrl, done);
+    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(collect, dim3(cblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, ctrl, cand, tie, ent);
+    hipLaunchKernelGGL(refine, dim3(1), dim3(kThreads), 0, s, ctrl, cand, tie, 0u);
+    // at most n_out + kSelSmall <= kCandCap seeds
+    const uint32_t max_seeds = (uint32_t)n_out + (uint32_t)kSelSmall;
+    hipLaunchKernelGGL(seed_rank, dim3((max_seeds + kSeedRankThreads / 16 - 1) / (kSeedRankThreads / 16)), dim3(kSeedRankThreads),
+                       (size_t)max_seeds * sizeof(uint64_t), s, scores, L, ctrl, cand, 2 * r_max, rank, dom_left, dom_right);
+    hipLaunchKernelGGL(seed_lists, dim3(n), dim3(kThreads), 2 * (size_t)kCandCap * sizeof(uint32_t), s, sp, L, ctrl, cand, rank,
+                       dom_left, dom_right, ctrl + 2, cand);
+    hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl + 2, cand + kCandCap, n, n_out, picked, picked_n);
+    hipLaunchKernelGGL(emit_sorted, emit_grid, dim3(kEmitThreads), 0, s, picked, picked_n, n_out, job.sink, out_idx, out_count);
+    return hipGetLastError();
+}
+
+}  // namespace
 
 hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
                          void *workspace, const SelectLayout &lay, hipStream_t s)
@@ -1110,32 +1170,25 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
     uint64_t *cand = (uint64_t *)(ws + lay.cand);
     uint64_t *tie = (uint64_t *)(ws + lay.tie);
     float *cells = (float *)(ws + lay.cells);
-    const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + 2 * (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
-    int bucket_shift = 0;
-    while (((int64_t)kBuckets << bucket_shift) < L) ++bucket_shift;
+    const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
+    uint32_t *picked = (uint32_t *)(ws + lay.picked), *picked_n = picked + ILRE_MAX_BUDGET;
+    const dim3 emit_grid((unsigned)((n_out + kEmitThreads / 16 - 1) / (kEmitThreads / 16)) + 1u);
 
-    // Dynamic LDS ceilings are the same constants on every call (idempotent, so concurrent callers agree).
-    constexpr int kPoolLdsMax = kPoolWaves * 2 * (kSelFine + 2 * (ILRE_MAX_AVG_KERNEL > ILRE_MAX_POOL_KERNEL ? ILRE_MAX_AVG_KERNEL : ILRE_MAX_POOL_KERNEL)) * (int)sizeof(float);
-    constexpr int kSortLdsMax = 16384 * (int)sizeof(uint64_t);  // >= ILRE_MAX_BUDGET + 1 keys, padded to a power of two
-    hipError_t e;
-    if ((e = hipFuncSetAttribute((const void *)allocate, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)allocate_ranked, hipFuncAttributeMaxDynamicSharedMemorySize, (int)alloc_lds)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)pool_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)pool_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)collect, hipFuncAttributeMaxDynamicSharedMemorySize, kPoolLdsMax)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)refine, hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsMax)) != hipSuccess) return e;
+    hipError_t e = set_select_attributes();
+    if (e != hipSuccess) return e;
     if (L == 0) {  // nothing but the sink part
-        hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, 0, 0, job.sink, 0, out_idx, out_count);
+        hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, 0, 0, picked, picked_n);
+        hipLaunchKernelGGL(emit_sorted, emit_grid, dim3(kEmitThreads), 0, s, picked, picked_n, 0, job.sink, out_idx, out_count);
         return hipGetLastError();
     }
+    if (job.mode == kSelWindowMax) return launch_select_window(scores, job, out_idx, out_count, ws, lay, s);
 
-    // B_c: floor(B / n), the first B mod n combinations one more.  K_j: window-max form, what the
-    // earlier shares could have taken plus the own share; printed form, K_m = B / m + 1 cells.
+    // The algorithm as printed.  B_c: floor(B / n), the first B mod n combinations one more; K_m = B / m + 1 cells.
     SelParams prm{};
     CellParams cp{};
     prm.n = n;
     prm.op = (uint32_t)job.mode;
-    prm.exact = job.mode == kSelMaxAvg ? 1u : 0u;
+    prm.exact = 1u;
     const int base = budget / n, rem = budget % n;
     int64_t before = 0, tie_off = 0, len_max = 0;
     int halo_max = 0;
@@ -1150,99 +1203,47 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
         prm.cell[j] = (uint32_t)cell;
         prm.tie_off[j] = (uint64_t)tie_off;
         tie_off += 2 * len;
-        if (job.mode == kSelMaxAvg) {
-            const int i = j / job.n_avg, na = job.avg_kernels[j % job.n_avg];
-            if (j % job.n_avg == 0) {
-                cp.m[i] = (uint32_t)cell;
-                cp.len[i] = (uint32_t)len;
-                cp.off[i] = cell_off;
-                cell_off += (uint64_t)len;
-            }
-            // K_m = B / m + 1 cells are candidates; of those the walk can only reach the first
-            // ceil((shares up to and including this one) / m): at most (shares before) tokens are taken
-            // when it starts and it stops after B_c free ones.  Only that many are found and sorted.
-            int64_t km = (int64_t)budget / cell + 1;
-            const int64_t reach = (before + share + cell - 1) / cell;
-            if (reach < km) km = reach;
-            prm.want[j] = (uint32_t)(km < len ? km : len);
-            prm.before[j] = (uint32_t)((na - 1) / 2);
-            prm.after[j] = (uint32_t)(na / 2);
-            prm.src_off[j] = cp.off[i];
-        } else {
-            const int64_t want = before + share < L ? before + share : L;
-            prm.want[j] = (uint32_t)want;
-            prm.before[j] = prm.after[j] = (uint32_t)((job.max_kernels[j] - 1) / 2);
-            prm.src_off[j] = 0;
+        const int i = j / job.n_avg, na = job.avg_kernels[j % job.n_avg];
+        if (j % job.n_avg == 0) {
+            cp.m[i] = (uint32_t)cell;
+            cp.len[i] = (uint32_t)len;
+            cp.off[i] = cell_off;
+            cell_off += (uint64_t)len;
         }
+        // K_m = B / m + 1 cells are candidates; of those the walk can only reach the first
+        // ceil((shares up to and including this one) / m): at most (shares before) tokens are taken
+        // when it starts and it stops after B_c free ones.  Only that many are found and sorted.
+        int64_t km = (int64_t)budget / cell + 1;
+        const int64_t reach = (before + share + cell - 1) / cell;
+        if (reach < km) km = reach;
+        prm.want[j] = (uint32_t)(km < len ? km : len);
+        prm.before[j] = (uint32_t)((na - 1) / 2);
+        prm.after[j] = (uint32_t)(na / 2);
+        prm.src_off[j] = cp.off[i];
         before += share;
         if ((int)(prm.before[j] + prm.after[j]) > halo_max) halo_max = (int)(prm.before[j] + prm.after[j]);
         if (len > len_max) len_max = len;
     }
     cp.n = job.n_max;
-    uint32_t sort_n = 0;  // printed form: candidates are sorted in LDS, padded to a power of two
-    if (job.mode == kSelMaxAvg) {
-        sort_n = 2;
-        for (int j = 0; j < n; ++j)
-            while (sort_n < prm.want[j]) sort_n *= 2;
-    }
-    const float *vals = job.mode == kSelMaxAvg ? cells : scores;
+    uint32_t sort_n = 2;  // candidates are sorted in LDS, padded to a power of two
+    for (int j = 0; j < n; ++j)
+        while (sort_n < prm.want[j]) sort_n *= 2;
     const uint32_t nfine = (uint32_t)((len_max + kSelFine - 1) / kSelFine);
     const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)(kSelFine + halo_max) * sizeof(float);
-    // Workgroups per combination in the pooling passes; beyond the cap the wavefronts loop over the
-    // entries.  A histogram workgroup carries fixed work (clearing and flushing 2048 bins, one atomic per
-    // hot bin on a handful of addresses, about 13 ns each and serialised, the completion counter), so
-    // those passes aim at about one resident round of workgroups over all combinations.
-    auto pool_blocks = [](uint32_t entries, uint32_t cap) {
-        const uint32_t want = (entries + kPoolWaves - 1) / kPoolWaves;
-        return want < cap ? (want ? want : 1u) : cap;
-    };
-    auto clamp_u32 = [](uint32_t x, uint32_t lo, uint32_t hi) { return x < lo ? lo : (x > hi ? hi : x); };
-    constexpr uint32_t kHistGrid = 2560, kCollectGrid = 8192;
-
-    Entries ent{nullptr, nullptr};
-    uint32_t entries = nfine;
-    if (job.mode == kSelMaxAvg) {
-        uint32_t cb = (uint32_t)((len_max + kPoolThreads - 1) / kPoolThreads);
-        if (cb > 2048u) cb = 2048u;
-        if (cb) hipLaunchKernelGGL(cell_max, dim3(cb, job.n_max), dim3(kPoolThreads), 0, s, scores, cp, cells);
-    } else if ((int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384) {
-        // Long contexts: visit only the fine chunks that can hold an admitted token.
-        float *cm = (float *)(ws + lay.cmax);
-        uint32_t *active = (uint32_t *)(ws + lay.active);
-        uint32_t *phist = hist + 2 * (size_t)n * kSelBins;
-        SelCtrl *pctrl = ctrl + n;
-        uint32_t *pdone = done + 2 * (size_t)n;
-        SelParams pp{};
-        pp.n = 1;
-        pp.len[0] = nfine;
-        pp.cell[0] = 1;
-        pp.want[0] = (uint32_t)n_out;
-        const uint32_t nfine2 = (nfine + kSelFine - 1) / kSelFine;
-        const Entries all{nullptr, nullptr};
-        const size_t lds0 = (size_t)kPoolWaves * 2 * kSelFine * sizeof(float);
-        hipLaunchKernelGGL(chunk_max, dim3(2048), dim3(kPoolThreads), 0, s, scores, L, nfine, cm);
-        hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, pp, phist, pctrl, pdone);
-        hipLaunchKernelGGL(pool_hist<1>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, 1, pctrl, phist, pdone, all);
-        hipLaunchKernelGGL(pool_hist<2>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), lds0, s, cm, 1, pctrl, phist, pdone, all);
-        const int reach = (halo_max / 2 + kSelFine - 1) / kSelFine;
-        hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, cm, nfine, reach, pctrl, active);
-        ent = Entries{active, &pctrl->cand_n};
-        // with a list the entry count is only known on the device: size the grid for the worst case the
-        // pruning rule is meant for (a few times the budget) and let the wavefronts loop
-        entries = 4u * (uint32_t)n_out + 1024u;
-    }
+    const Entries ent{nullptr, nullptr};
+    uint32_t cb = (uint32_t)((len_max + kPoolThreads - 1) / kPoolThreads);
+    if (cb > 2048u) cb = 2048u;
+    if (cb) hipLaunchKernelGGL(cell_max, dim3(cb, job.n_max), dim3(kPoolThreads), 0, s, scores, cp, cells);
     const uint32_t hcap = clamp_u32(kHistGrid / (uint32_t)n, 32u, 256u), ccap = clamp_u32(kCollectGrid / (uint32_t)n, 64u, 1024u);
-    const uint32_t hblocks = pool_blocks(entries, hcap), cblocks = pool_blocks(entries, ccap);
+    const uint32_t hblocks = pool_blocks(nfine, hcap), cblocks = pool_blocks(nfine, ccap);
 
     hipLaunchKernelGGL(sel_init, dim3(n), dim3(kThreads), 0, s, prm, hist, ctrl, done);
-    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, vals, n, ctrl, hist, done, ent);
-    hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, vals, n, ctrl, hist, done, ent);
-    hipLaunchKernelGGL(collect, dim3(cblocks, n), dim3(kPoolThreads), pool_lds, s, vals, ctrl, cand, tie, ent);
+    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, cells, n, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, n), dim3(kPoolThreads), pool_lds, s, cells, n, ctrl, hist, done, ent);
+    hipLaunchKernelGGL(collect, dim3(cblocks, n), dim3(kPoolThreads), pool_lds, s, cells, ctrl, cand, tie, ent);
     hipLaunchKernelGGL(refine, dim3(n), dim3(kThreads), (size_t)sort_n * sizeof(uint64_t), s, ctrl, cand, tie, sort_n);
-    if (job.mode == kSelMaxAvg)
-        hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, n, n_out, job.sink, bucket_shift, out_idx, out_count);
-    else
-        hipLaunchKernelGGL(allocate, dim3(1), dim3(kThreads), alloc_lds, s, ctrl, cand, n, n_out, job.sink, bucket_shift, out_idx, out_count);
+    hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, n, n_out, picked, picked_n);
+    hipLaunchKernelGGL(emit_sorted, emit_grid, dim3(kEmitThreads), 0, s, picked, picked_n, n_out, job.sink, out_idx, out_count);
     return hipGetLastError();
 }
 

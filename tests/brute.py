@@ -37,14 +37,16 @@ def brute_pool(score, w):
     return [max(score[u] for u in range(max(0, t - r), min(L, t + r + 1))) for t in range(L)]
 
 
-def brute_allocate(score, kernels, budget):
+def brute_allocate(score, kernels, budget, sink=0):
+    """Algorithm 1, stride-1 max-pool reading: the sink tokens are in I from the start and the pooling
+    never sees them; every other token is walked in rank order per kernel size."""
     L = len(score)
     n = len(kernels)
     shares = [budget // n + (1 if j < budget % n else 0) for j in range(n)]
-    chosen = set()
+    chosen = set(range(sink))
     for w, share in zip(kernels, shares):
-        pooled = brute_pool(score, w)
-        ranked = sorted(range(L), key=lambda t: (-pooled[t], t))
+        pooled = [None] * sink + brute_pool(score[sink:], w)
+        ranked = sorted(range(sink, L), key=lambda t: (-pooled[t], t))
         got = 0
         for t in ranked:
             if got >= share:

@@ -27,8 +27,9 @@ def test_header_symbols_are_exported():
 
 
 def test_opts_struct_matches_header_layout():
-    # int32 x4, float, int32, int64 x4, pointer, size_t, pointer on LP64
-    assert ctypes.sizeof(binding.IlreOpts) == 4 * 4 + 4 + 4 + 8 * 4 + 8 + 8 + 8
+    # int32 x4, float, int32, int64 x4, pointer, size_t, pointer, int32 x2 on LP64
+    assert ctypes.sizeof(binding.IlreOpts) == 4 * 4 + 4 + 4 + 8 * 4 + 8 + 8 + 8 + 4 + 4
+    assert binding.IlreOpts.sink.offset == 80
     assert binding.IlreOpts.k_stride_head.offset == 24
     assert binding.IlreOpts.workspace.offset == 56
 

@@ -154,6 +154,54 @@ def test_select_exact_on_given_scores(name, L, kernels, budget, kind):
     assert got.tolist() == want.tolist()
 
 
+SINK_CASES = [
+    # name, L, sink, kernels, budget, kind
+    ("paper_sink_needles", 100000, 4, (1, 3, 7, 15, 31), 4096, "needles"),
+    ("sink_scores_dominate", 20000, 5, (3, 7, 15), 1000, "random"),
+    ("sink_is_everything", 37, 37, (3,), 16, "random"),
+    ("sink_leaves_one_token", 38, 37, (3, 7), 16, "random"),
+    ("sink_and_budget_exceed_L", 300, 4, (3, 7), 1000, "random"),
+    ("sink_all_equal", 10000, 3, (3, 7, 15), 100, "equal"),
+    ("sink_pruned_long_context", 4500001, 4, (1, 3, 7, 15, 31), 4096, "needles"),
+]
+
+
+@pytest.mark.parametrize("name,L,sink,kernels,budget,kind", SINK_CASES, ids=[c[0] for c in SINK_CASES])
+def test_select_with_a_sink_part(name, L, sink, kernels, budget, kind):
+    """Window-max form with the sink part of Algorithm 1: the first `sink` tokens always kept and invisible to
+    the pooling (their scores are set far above everything else, so any leak would show), the budget counting
+    the others; bit-exact with the oracle."""
+    _announce(f"select with sink {name} L={L} sink={sink} kernels={kernels} budget={budget}")
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    s = _scores_for(kind, L, rng) if L > 300 else rng.random(L).astype(np.float32)
+    s[:sink] = 1000.0
+    want = oracle.allocate(s, kernels, budget, sink=sink)
+    got = il.ilre_select(torch.from_numpy(s).cuda(), budget, kernels, sink=sink)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert got.shape == (sink + min(budget, L - sink),) and got.dtype == np.int32
+    assert got.tolist() == want.tolist()
+
+
+def test_recall_with_a_sink_part():
+    """Whole path with a sink part: same scores as without (Eq. 4 runs over all L positions), selection equal to
+    the staged call and to the oracle's Algorithm 1 on the GPU's own scores."""
+    _announce("end_to_end with sink 4 (ragged bf16)")
+    inp = inputs.custom(L=9001, Lq=40, Hq=16, Hkv=4, d=128, dtype="bf16", n_spans=3, span_len=(16, 40),
+                        channel_scale=True, seed=78)
+    q, k = to_device(inp.q), to_device(inp.k)
+    kernels, budget, sink = (1, 3, 7, 15, 31), 512, 4
+    idx, scores = il.ilre_recall(q, k, budget, kernels, sink=sink)
+    _, plain_scores = il.ilre_recall(q, k, budget, kernels)
+    staged = il.ilre_select(scores, budget, kernels, sink=sink)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, plain_scores) and torch.equal(idx, staged)
+    assert idx.cpu().numpy().tolist() == oracle.allocate(scores.cpu().numpy(), kernels, budget, sink=sink).tolist()
+    want_scores, _, _ = oracle.scores(inp.q, inp.k)
+    bad, worst = score_errors(scores.cpu().numpy(), want_scores)
+    assert bad == 0, worst
+
+
 PAPER_MAX, PAPER_AVG = (2, 4, 8), tuple(range(1, 17))     # the paper's default pooling set (Section 3.2)
 
 MAX_AVG_CASES = [
@@ -444,10 +492,11 @@ def test_select_randomised_against_oracle(seed):
         if case % 2 == 0:
             n = int(rng.integers(1, 7))
             kernels = tuple(int(2 * rng.integers(0, 40) + 1) for _ in range(n))
-            want = oracle.allocate(s, kernels, budget)
-            got = il.ilre_select(dev, budget, kernels)
+            sink = int(rng.integers(0, min(L, 6) + 1)) if case % 4 == 0 else 0
+            want = oracle.allocate(s, kernels, budget, sink=sink)
+            got = il.ilre_select(dev, budget, kernels, sink=sink)
             torch.cuda.synchronize()
-            assert got.cpu().numpy().tolist() == want.tolist(), (seed, case, L, kind, budget, kernels)
+            assert got.cpu().numpy().tolist() == want.tolist(), (seed, case, L, kind, budget, kernels, sink)
         else:
             mk = tuple(int(rng.integers(1, 20)) for _ in range(int(rng.integers(1, 4))))
             ak = tuple(int(rng.integers(1, 24)) for _ in range(int(rng.integers(1, 5))))

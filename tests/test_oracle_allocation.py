@@ -191,3 +191,22 @@ def test_thresholds_max_avg_replay():
     th2 = oracle.thresholds_max_avg(s[:1003], [4], [1], 50, sink=0)
     assert np.isnan(th2[0][0][1000:]).all() and not np.isnan(th2[0][0][:1000]).any()
     assert th2[0][2] == float(np.sort(s[:1000].reshape(250, 4).max(axis=1))[::-1][50 // 4])
+
+
+def test_allocate_with_a_sink_part_against_brute_force():
+    """The sink tokens are always kept, the pooling windows stop at the sink boundary (a high sink score must not
+    leak into its neighbours' pooled values) and the budget counts the other tokens."""
+    rng = np.random.default_rng(41)
+    for case in range(30):
+        L = int(rng.integers(5, 60))
+        sink = int(rng.integers(0, min(L, 6) + 1))
+        s = (rng.integers(1, 12, size=L) / 16.0).astype(np.float32) if case % 2 else rng.random(L).astype(np.float32)
+        s[:sink] = 50.0                                   # would win every window it leaked into
+        kernels = [int(2 * rng.integers(0, 5) + 1) for _ in range(int(rng.integers(1, 4)))]
+        budget = int(rng.integers(1, L + 3))
+        got = oracle.allocate(s, kernels, budget, sink=sink)
+        assert got.tolist() == brute_allocate([float(x) for x in s], kernels, budget, sink=sink)
+        assert got[:sink].tolist() == list(range(sink)) and len(got) == sink + min(budget, L - sink)
+    # hand-worked: scores 9 9 | 1 5 1 1 4 1, sink 2, kernel 3, budget 3 -> body pooled 5 5 5 4 4 4 -> body tokens 0 1 2
+    s = np.array([9, 9, 1, 5, 1, 1, 4, 1], dtype=np.float32)
+    assert oracle.allocate(s, [3], 3, sink=2).tolist() == [0, 1, 2, 3, 4]
