@@ -177,7 +177,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="workload number (1-5); the metric is quoted on 5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-row-divisor", type=int, default=8,
+    ap.add_argument("--cpu-row-divisor", type=int, default=2,
                     help="the cpu_baseline leg runs the oracle on all context tokens and 1/divisor of the query tokens")
     ap.add_argument("--no-configs", action="store_true", help="skip the lines for the other workloads (cfg 2-4)")
     ap.add_argument("--traffic-bytes", type=float, default=None,

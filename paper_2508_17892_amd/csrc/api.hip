@@ -199,6 +199,17 @@ int fill_qk(ilre::ScoreArgs &a, const void *q, const void *k, int64_t L, int32_t
     return ILRE_OK;
 }
 
+// The key stream addresses a tile's rows with 32-bit byte offsets from the tile's first token.
+int check_tile_span(const ilre::ScoreArgs &a, const ilre::ScorePlan &p, int dtype)
+{
+    const int64_t es = dtype == ILRE_BF16 ? 2 : 4;
+    const int64_t span = a.k_stride_token * es * (int64_t)(p.tile_tokens - 1) + (int64_t)ILRE_HEAD_DIM * es;
+    if (span > 0x7FFFFFFFll)
+        return fail(ILRE_EUNSUPPORTED, "k_stride_token %lld too large: a tile of %d tokens would span %lld bytes (limit 2^31 - 1)",
+                    (long long)a.k_stride_token, p.tile_tokens, (long long)span);
+    return ILRE_OK;
+}
+
 void fill_plan(ilre::ScoreArgs &a, const ilre::ScorePlan &p)
 {
     a.rows_per_group = p.rows_per_group;
@@ -262,6 +273,7 @@ int row_stats_into(const void *q, const void *k_cache, int64_t L, int32_t Lq, in
     }
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    if ((rc = check_tile_span(a, p, opts->dtype))) return rc;
     fill_plan(a, p);
     a.part_m = (float *)(ws + lay.part_m);
     a.part_z = (float *)(ws + lay.part_z);
@@ -328,6 +340,7 @@ int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, i
     if ((rc = check_workspace(opts, lay.select))) return rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    if ((rc = check_tile_span(a, p, opts->dtype))) return rc;
     fill_plan(a, p);
     unsigned char *ws = (unsigned char *)opts->workspace;
     a.row_max = row_max;
@@ -387,6 +400,7 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     int rc;
     ilre::ScoreArgs a{};
     if ((rc = fill_qk(a, q, k_cache, L, Lq, Hq, Hkv, d, opts))) return rc;
+    if ((rc = check_tile_span(a, p, opts->dtype))) return rc;
     fill_plan(a, p);
     unsigned char *ws = (unsigned char *)opts->workspace;
     hipStream_t s = (hipStream_t)opts->stream;

@@ -17,8 +17,25 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 namespace {
 
+// 2^x without the transcendental unit: x = i + f with i = round(x), f in [-0.5, 0.5]; 2^f by a degree-4
+// polynomial (relative error about 4e-6), times 2^i by adding i to the exponent field.
+__device__ __forceinline__ float poly_exp2(float x)
+{
+    const float magic = 12582912.0f;  // 1.5 * 2^23: the sum's low mantissa bits hold round(x)
+    const float t = x + magic;
+    const float f = x - (t - magic);
+    float p = 9.6181291e-3f;
+    p = __builtin_fmaf(p, f, 5.5504109e-2f);
+    p = __builtin_fmaf(p, f, 2.4022651e-1f);
+    p = __builtin_fmaf(p, f, 6.9314718e-1f);
+    p = __builtin_fmaf(p, f, 1.0f);
+    return __uint_as_float(__float_as_uint(p) + (__float_as_uint(t) << 23));
+}
+
 // VALU: 0 none (MFMAs only), 1 fma + exp2 + add per accumulator element (the kernels' mix),
-//       2 fma + add only, 3 exp2 + add only
+//       2 fma + add only, 3 exp2 + add only,
+//       4 the mix with every exp2 computed on the plain vector pipe (round, subtract, degree-4 polynomial,
+//         exponent add: 8 plain instructions in place of one transcendental), 5 every other exp2 so
 // MFMA: false = the vector work alone, on accumulators the compiler must take as new data every unit
 //       (rates are then quoted for the MFMAs that were left out)
 template <int NB, int WAVES, int VALU, bool MFMA = true>
@@ -84,11 +101,15 @@ __global__ __launch_bounds__(WAVES * 64) void ceiling_kernel(const uint4 *src, i
                         if (VALU == 1) p[v & 3] += __builtin_amdgcn_exp2f(__builtin_fmaf(a[v], c, off));
                         if (VALU == 2) p[v & 3] += __builtin_fmaf(a[v], c, off);
                         if (VALU == 3) p[v & 3] += __builtin_amdgcn_exp2f(a[v]);
+                        if (VALU == 4) p[v & 3] += poly_exp2(__builtin_fmaf(a[v], c, off));
+                        if (VALU == 5)
+                            p[v & 3] += (v & 1) ? poly_exp2(__builtin_fmaf(a[v], c, off))
+                                                : __builtin_amdgcn_exp2f(__builtin_fmaf(a[v], c, off));
                     }
                     z[b] += (p[0] + p[1]) + (p[2] + p[3]);
                 }
                 // one MFMA, then its share of the vector work, as in the scoring kernels
-                constexpr int kPerMfma = VALU == 1 ? 6 : 4;
+                constexpr int kPerMfma = VALU == 1 ? 6 : (VALU == 4 ? 22 : (VALU == 5 ? 14 : 4));
                 if (MFMA) {
 #pragma unroll
                     for (int st = 0; st < 8; ++st)
@@ -131,6 +152,8 @@ const Variant kVariants[] = {
     {2, 8, 3, "8 wavefronts x 64 rows, exp2 + add per logit"},
     {1, 16, 1, "the mix: 16 wavefronts x 32 rows, 4 per SIMD"},
     {1, 16, 0, "MFMAs only: 16 wavefronts x 32 rows, 4 per SIMD"},
+    {2, 8, 4, "8 wavefronts x 64 rows, the mix with exp2 as 8 plain vector instructions (no transcendental)"},
+    {2, 8, 5, "8 wavefronts x 64 rows, the mix with every other exp2 as 8 plain vector instructions"},
     {2, 8, 1, "no MFMAs: the vector work of the mix alone (fma + exp2 + add per logit), 8 wavefronts; rate quoted for the MFMAs left out", false},
     {2, 8, 2, "no MFMAs: fma + add per logit alone, 8 wavefronts", false},
     {2, 8, 3, "no MFMAs: exp2 + add per logit alone, 8 wavefronts", false},
@@ -161,6 +184,8 @@ hipError_t launch_probe(int variant, int iters, const void *operands, float *out
     ILRE_PROBE(2, 8, 3)
     ILRE_PROBE(1, 16, 1)
     ILRE_PROBE(1, 16, 0)
+    ILRE_PROBE(2, 8, 4)
+    ILRE_PROBE(2, 8, 5)
 #undef ILRE_PROBE
     if (!v.mfma && v.valu == 1) hipLaunchKernelGGL((ceiling_kernel<2, 8, 1, false>), grid, block, 0, s, src, iters, c, out, clocks);
     if (!v.mfma && v.valu == 2) hipLaunchKernelGGL((ceiling_kernel<2, 8, 2, false>), grid, block, 0, s, src, iters, c, out, clocks);

@@ -222,6 +222,25 @@ __device__ __forceinline__ Pooling pooling_of(const float *vals, const SelCtrl &
 }
 __device__ __forceinline__ size_t pool_lds_floats(int before, int after) { return (size_t)(kSelFine + before + after); }
 
+// Window 1 in the window-max form (the seed pass): the pooled value is the element.  kRawBatch fine chunks
+// (entries e0 .. e0 + kRawBatch - 1 of the visit list) are fetched at once; fcs[u] < 0 marks a missing entry.
+constexpr int kRawBatch = 4;
+__device__ __forceinline__ bool raw_window(const Pooling &pl) { return pl.op == kSelWindowMax && pl.before + pl.after == 0; }
+__device__ __forceinline__ void raw_fetch(const Pooling &pl, const Entries &ent, uint32_t e0, uint32_t nent, int64_t (&fcs)[kRawBatch],
+                                          float (&vals)[kRawBatch][kPerThread])
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < kRawBatch; ++u) fcs[u] = e0 + u < nent ? (int64_t)entry_chunk(ent, e0 + u) : -1;
+#pragma unroll
+    for (int u = 0; u < kRawBatch; ++u)
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int64_t e = (fcs[u] < 0 ? 0 : fcs[u]) * kSelFine + lane + k * 64;
+            vals[u][k] = pl.src[e < pl.len ? e : pl.len - 1];  // lanes past the end are ignored by the callers
+        }
+}
+
 // Pooled values of this lane's kPerThread elements (lane + 64k) of fine chunk `fc`, computed by one
 // wavefront in its own LDS buffers b0/b1 (kSelFine + before + after floats each).
 //   kSelWindowMax: pooled[e] = max(src[u] : e - before <= u <= e + after, 0 <= u < len)  (MaxPooling at
@@ -232,16 +251,6 @@ __device__ __forceinline__ size_t pool_lds_floats(int before, int after) { retur
 __device__ __forceinline__ void pooled_wave(const Pooling &pl, int64_t fc, float *b0, float *b1, float (&out)[kPerThread])
 {
     const int lane = threadIdx.x & 63;
-    if (pl.op == kSelWindowMax && pl.before + pl.after == 0) {
-        // window 1 (the seed pass of the window-max form): the elements themselves, no trip through LDS
-        // (callers ignore the lanes past the end of the array)
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            const int64_t e = fc * kSelFine + lane + k * 64;
-            out[k] = pl.src[e < pl.len ? e : pl.len - 1];
-        }
-        return;
-    }
     const int len = kSelFine + pl.before + pl.after;
     const int64_t first = fc * kSelFine - pl.before;
     const float pad = pl.op == kSelMaxAvg ? 0.0f : -INFINITY;
@@ -374,10 +383,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int
     for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
     __syncthreads();
     const uint32_t nent = entry_count(ent, (uint32_t)pl.len);
-    for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
-        const int64_t fc = entry_chunk(ent, e);
-        float pooled[kPerThread];
-        pooled_wave(pl, fc, b0, b1, pooled);
+    auto account = [&](const float (&pooled)[kPerThread], int64_t fc) {
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const int64_t el = fc * kSelFine + lane + k * 64;
@@ -403,22 +409,48 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int
                 atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
             }
         }
+    };
+    if (raw_window(pl)) {
+        // window 1: the elements themselves; a wavefront fetches kRawBatch fine chunks before it accounts for
+        // any, so that their loads are in flight together
+        for (uint32_t e0 = (blockIdx.x * kPoolWaves + wave) * kRawBatch; e0 < nent; e0 += gridDim.x * kPoolWaves * kRawBatch) {
+            float vals_[kRawBatch][kPerThread];
+            int64_t fcs[kRawBatch];
+            raw_fetch(pl, ent, e0, nent, fcs, vals_);
+#pragma unroll
+            for (int u = 0; u < kRawBatch; ++u)
+                if (fcs[u] >= 0) account(vals_[u], fcs[u]);  // uniform
+        }
+    } else {
+        for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
+            const int64_t fc = entry_chunk(ent, e);
+            float pooled[kPerThread];
+            pooled_wave(pl, fc, b0, b1, pooled);
+            account(pooled, fc);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) {
         const uint32_t c = lh[i];
         if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
     }
-    // The last workgroup of combination j to get here sees its histogram complete and locates the bin.  Each
-    // thread waits until its histogram atomics have been performed, then one thread counts the workgroup in
-    // (fences here cost tens of microseconds: an agent-scope release writes the L2 back).
+    // The last workgroup of combination j to get here sees its histogram complete and locates the bin.  The
+    // bins are only ever touched by device-scope atomics (adds here, atomic loads in find_bins), which are
+    // performed at the memory side, common to all eight L2s.  Each thread waits until its adds have been
+    // performed (vmcnt counts them), then one thread counts the workgroup in with another device-scope atomic:
+    // whoever reads the final count reads, with atomic loads issued after it, bins that hold every add.  A
+    // device-scope release fence in their place would also write this L2's unrelated dirty lines back, tens of
+    // microseconds per workgroup; the acquire side, one workgroup per combination, is cheap and is there.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0)
         is_last = __hip_atomic_fetch_add(&done[(LEVEL - 1) * n + j], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   gridDim.x - 1;
     __syncthreads();
-    if (is_last) find_bins<LEVEL>(hist, ctrl, j);
+    if (is_last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        find_bins<LEVEL>(hist, ctrl, j);
+    }
 }
 
 __global__ __launch_bounds__(kPoolThreads) void collect(const float *vals, SelCtrl *ctrl, uint64_t *cand, uint64_t *tie,
@@ -436,10 +468,7 @@ __global__ __launch_bounds__(kPoolThreads) void collect(const float *vals, SelCt
     uint64_t *cand_j = cand + (size_t)j * kCandCap;
     uint64_t *tie_j = tie + ctrl[j].tie_off;
     const uint32_t nent = entry_count(ent, (uint32_t)pl.len);
-    for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
-        const int64_t fc = entry_chunk(ent, e);
-        float pooled[kPerThread];
-        pooled_wave(pl, fc, b0, b1, pooled);
+    auto sort_out = [&](const float (&pooled)[kPerThread], int64_t fc) {
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const int64_t el = fc * kSelFine + lane + k * 64;
@@ -448,6 +477,23 @@ __global__ __launch_bounds__(kPoolThreads) void collect(const float *vals, SelCt
             const uint64_t key = make_key(pooled[k], (uint32_t)el);
             wave_append(valid && p22 > prefix, key, cand_j, &ctrl[j].cand_n);
             wave_append(valid && p22 == prefix, key, tie_j, &ctrl[j].tie_n);
+        }
+    };
+    if (raw_window(pl)) {
+        for (uint32_t e0 = (blockIdx.x * kPoolWaves + wave) * kRawBatch; e0 < nent; e0 += gridDim.x * kPoolWaves * kRawBatch) {
+            float vals_[kRawBatch][kPerThread];
+            int64_t fcs[kRawBatch];
+            raw_fetch(pl, ent, e0, nent, fcs, vals_);
+#pragma unroll
+            for (int u = 0; u < kRawBatch; ++u)
+                if (fcs[u] >= 0) sort_out(vals_[u], fcs[u]);  // uniform
+        }
+    } else {
+        for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
+            const int64_t fc = entry_chunk(ent, e);
+            float pooled[kPerThread];
+            pooled_wave(pl, fc, b0, b1, pooled);
+            sort_out(pooled, fc);
         }
     }
 }
@@ -1129,15 +1175,18 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
         const Entries all{nullptr, nullptr};
         hipLaunchKernelGGL(chunk_max, dim3(2048), dim3(kPoolThreads), 0, s, scores, L, nfine, cm);
         hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, pp, phist, pctrl, pdone);
-        hipLaunchKernelGGL(pool_hist<1>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
-        hipLaunchKernelGGL(pool_hist<2>, dim3(pool_blocks(nfine2, 1024), 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
+        const uint32_t pblocks = pool_blocks((nfine2 + kRawBatch - 1) / kRawBatch, 1024);
+        hipLaunchKernelGGL(pool_hist<1>, dim3(pblocks, 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
+        hipLaunchKernelGGL(pool_hist<2>, dim3(pblocks, 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
         hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, cm, nfine, 0, pctrl, active);
         ent = Entries{active, &pctrl->cand_n};
         // with a list the entry count is only known on the device: size the grid for the worst case the
         // pruning rule is meant for (a few times the budget) and let the wavefronts loop
         entries = 4u * (uint32_t)n_out + 1024u;
     }
-    const uint32_t hblocks = pool_blocks(entries, 256u), cblocks = pool_blocks(entries, 1024u);
+    // window 1: a wavefront takes kRawBatch fine chunks per round
+    const uint32_t batches = (entries + kRawBatch - 1) / kRawBatch;
+    const uint32_t hblocks = pool_blocks(batches, 256u), cblocks = pool_blocks(batches, 1024u);
     hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, prm, hist, ctrl, done);
     hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
     hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
