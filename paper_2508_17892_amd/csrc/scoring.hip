@@ -19,6 +19,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include <type_traits>
 
 namespace ilre {
@@ -511,10 +513,26 @@ constexpr size_t tile_lds_bytes(int waves)
     return 3 * (size_t)Traits<DT>::tile_tokens(waves) * (Traits<DT>::kChunksPerRow * 16);
 }
 
+// The dynamic-LDS ceiling of a kernel is raised once per process (to the most any plan asks of it: the
+// 8-wavefront tiles plus the partial-result buffers of pass 2), not on every launch.
+constexpr int kMaxDynamicLds = 160 * 1024;
+hipError_t raise_lds_limit_once(const void *kernel)
+{
+    static std::mutex mutex;
+    static const void *done[32];
+    static int ndone = 0;
+    std::lock_guard<std::mutex> lock(mutex);
+    for (int i = 0; i < ndone; ++i)
+        if (done[i] == kernel) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
+    if (e == hipSuccess && ndone < 32) done[ndone++] = kernel;
+    return e;
+}
+
 template <typename K>
 hipError_t launch_score(K kernel, int grid, int threads, size_t lds, const ScoreArgs &a, hipStream_t s)
 {
-    hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = raise_lds_limit_once((const void *)kernel);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, s, a);
     return hipGetLastError();
