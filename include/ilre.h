@@ -118,15 +118,15 @@ int ilre_recall(const void *q, const void *k_cache,
    exponentials against it, i.e. the softmax normaliser in two parts:
        row_sumexp[r] = sum_t exp(logit[r,t] - row_ref[r]),   log sum_t exp(logit[r,t]) = row_ref[r] + log row_sumexp[r].
    row_ref[r] <= max_t logit[r,t]; it equals the maximum with ILRE_FLAG_EXACT_ROW_MAX, otherwise it is
-   the maximum over the first tokens of the row's context splits (row_sumexp stays finite: rows whose
-   sums would leave the fp32 range are redone against the exact maximum).  Both dev, Hq*Lq float. */
+   the maximum over the first tokens of the row's context splits (row_sumexp stays finite: a part of the
+   context whose sums would leave the safe range is walked again against the running maximum).  Both dev, Hq*Lq float. */
 int ilre_row_stats(const void *q, const void *k_cache,
                    int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                    float *row_ref, float *row_sumexp, const ilre_opts *opts);
 
 /* ilre_row_stats for callers that cannot allocate device memory or pass a workspace: code running under HIP
    graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
-   bit-identical results; the per-split partial statistics and the overflow flag live in a buffer of
+   bit-identical results; the per-split partial statistics live in a buffer of
    ILRE_STATIC_SCRATCH_BYTES built into the library (one copy per GPU, held until the process ends) instead
    of opts->workspace, which is not read.  Makes no allocating call.  ILRE_EUNSUPPORTED when the shape needs
    more scratch than the buffer holds (2 * 4 bytes per query row and token split, plus 512; the 1M-token

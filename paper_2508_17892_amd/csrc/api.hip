@@ -9,7 +9,7 @@
 
 #include "ilre_internal.h"
 
-// Scratch of ilre_row_stats_static: the per-split partial row statistics and the overflow flag live here
+// Scratch of ilre_row_stats_static: the per-split partial row statistics live here
 // instead of in a caller's workspace.  One copy per GPU the library runs on, held until the process ends.
 // In host code this name is only a handle for hipGetSymbolAddress; the device address it yields is what
 // the kernels are given.
@@ -277,7 +277,6 @@ int row_stats_into(const void *q, const void *k_cache, int64_t L, int32_t Lq, in
     fill_plan(a, p);
     a.part_m = (float *)(ws + lay.part_m);
     a.part_z = (float *)(ws + lay.part_z);
-    a.overflow = (uint32_t *)(ws + lay.flag);
     const hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
     return ILRE_OK;
@@ -406,7 +405,6 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     hipStream_t s = (hipStream_t)opts->stream;
     a.part_m = (float *)(ws + lay.part_m);
     a.part_z = (float *)(ws + lay.part_z);
-    a.overflow = (uint32_t *)(ws + lay.flag);
     float *row_max = (float *)(ws + lay.row_max);
     float *row_sumexp = (float *)(ws + lay.row_sumexp);
     hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, s);

@@ -44,8 +44,7 @@ struct ScoreArgs {
     int64_t ntiles, tiles_per_split;
     // pass 1 (row statistics): per-split partial maxima (base-2 units) and sums
     float *part_m, *part_z;  // [nsplit][Hq*Lq]
-    uint32_t *overflow;      // flag: a frozen-reference sum left the fp32 range, redo with the safe form
-    int force_online;        // 1: follow the running maximum throughout (the safe form)
+    int force_online;        // 1: follow the running maximum throughout (the always-safe form)
     // pass 2 (column scores)
     const float *row_max, *row_sumexp;  // [Hq*Lq]
     float *partial;                     // [nunits][L]

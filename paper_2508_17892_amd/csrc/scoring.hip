@@ -31,6 +31,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 namespace {
 
 constexpr float kNegBig = -1.0e30f;
+// a partial sum against a frozen reference beyond this is redone against the running maximum: far above anything
+// a row with moderate logits reaches, far enough below the fp32 limit that merging 512 splits stays finite
+constexpr float kFrozenSumLimit = 1.0e30f;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -125,7 +128,7 @@ __device__ __forceinline__ float quad_swap2(float x)  // lanes 0<->2, 1<->3 of e
 
 // The same sum against a frozen reference m: no maximum, no rescale.  Any finite m gives the same
 // (m, z) pair up to rounding as long as 2^(x - m) stays in range; a row whose later logits exceed m by
-// more than ~2^7 base-2 units overflows to inf, which the caller detects and redoes with row_update.
+// more than ~2^7 base-2 units overflows to inf, which the kernel detects and redoes with row_update.
 __device__ __forceinline__ void row_accumulate(const f32x16 &acc, float c, float m, float (&z)[4])
 {
     const float nm = -m;
@@ -170,15 +173,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     const int64_t tile0 = (int64_t)split * a.tiles_per_split;
     const int64_t tile1 = (tile0 + a.tiles_per_split < a.ntiles) ? tile0 + a.tiles_per_split : a.ntiles;
     if (tile0 >= tile1) return;
-    if (MODE == 0 && a.overflow) {
-        // the redo launch runs only if the first attempt overflowed; the first attempt clears the flag
-        if (a.force_online) {
-            if (*a.overflow == 0) return;
-        } else if (blockIdx.x == 0 && threadIdx.x == 0) {
-            *a.overflow = 0;
-        }
-    }
-
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int lane = tid & 63;
@@ -241,8 +235,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // per-lane LDS byte offset of fragment chunk (2*st + half) of row l32 within a 32-row block,
     // relative to the tile buffer being read; advanced from buffer to buffer in place
     unsigned frag_addr[STEPS];
-#pragma unroll
-    for (int st = 0; st < STEPS; ++st) frag_addr[st] = lds0 + l32 * ROWB + (((2 * st + half) ^ (l32 & 15)) * 16);
 
     // pass-1 state: one (max, sum) per owned query row, in base-2 exponent units
     float m[NB], z[NB][4];
@@ -343,24 +335,28 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
         }
     };
 
-    // Prologue: the first two tiles go to buffers 0 and 1.
-    issue_tile(tile0, 0);
-    if (tile0 + 1 < tile1) issue_tile(tile0 + 1, 1);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    // acc[u & 1] receives unit u (a 32-token block against the wave's NB query blocks); the unit
-    // before the very first one is all -inf, which the softmax arithmetic turns into zeros.
     f32x16 acc[2][NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[1][b][v] = -INFINITY;
-    }
     uint4 kf[STEPS];
+    auto start_split = [&]() {
 #pragma unroll
-    for (int st = 0; st < STEPS; ++st)
-        kf[st] = *(const uint4 *)(__attribute__((address_space(3))) unsigned char *)(size_t)frag_addr[st];
+        for (int st = 0; st < STEPS; ++st) frag_addr[st] = lds0 + l32 * ROWB + (((2 * st + half) ^ (l32 & 15)) * 16);
+        // Prologue: the first two tiles go to buffers 0 and 1.
+        issue_tile(tile0, 0);
+        if (tile0 + 1 < tile1) issue_tile(tile0 + 1, 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+
+        // acc[u & 1] receives unit u (a 32-token block against the wave's NB query blocks); the unit
+        // before the very first one is all -inf, which the softmax arithmetic turns into zeros.
+    #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+    #pragma unroll
+            for (int v = 0; v < 16; ++v) acc[1][b][v] = -INFINITY;
+        }
+    #pragma unroll
+        for (int st = 0; st < STEPS; ++st)
+            kf[st] = *(const uint4 *)(__attribute__((address_space(3))) unsigned char *)(size_t)frag_addr[st];
+    };
 
     // One tile.  Its buffer and the next tile's are already published; the tile after that is
     // requested now and published by the barrier at the end.  Per 32-token block the NB independent
@@ -432,10 +428,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     // stored); the ragged tile, if any, is the last tile of the last split.
     const bool last_ragged = MODE == 0 && tile1 * TN > a.L;
     const int64_t tile_full_end = last_ragged ? tile1 - 1 : tile1;
-    // Pass 1 follows the running maximum for the first two tiles of its split, then freezes each
-    // row's reference and only accumulates (unless the caller asked for the always-safe form).
+    // One walk over the split.  Pass 1 follows the running maximum for the first two tiles, then freezes each
+    // row's reference and only accumulates -- unless `online_all`, the always-safe form.
+    auto run_split = [&](bool online_all) {
+    start_split();
     int64_t online_end = tile_full_end;
-    if (MODE == 0 && !a.force_online && tile0 + 2 < tile_full_end) online_end = tile0 + 2;
+    if (MODE == 0 && !online_all && tile0 + 2 < tile_full_end) online_end = tile0 + 2;
     int64_t tile = tile0;
     for (; tile < online_end; ++tile) do_tile(tile, std::false_type{}, std::false_type{});
     if (MODE == 0)
@@ -449,6 +447,26 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
             finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::true_type{}, std::false_type{});
         else
             finish_unit(acc[(UNITS - 1) & 1][b], b, UNITS - 1, tile1 - 1, rb_last, std::false_type{}, std::false_type{});
+    }
+    };
+    run_split(MODE == 0 && a.force_online);
+    if (MODE == 0 && !a.force_online) {
+        // A row whose later logits lie far above its frozen reference sums to inf (or to something a merge over
+        // the splits could push out of range): the workgroup then walks its split again, following the maximum.
+        bool bad = false;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bad = bad || !(z[b][k] <= kFrozenSumLimit);
+        if (__syncthreads_or(bad)) {  // uniform; also orders the last reads of the tile buffers before the new DMA
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                m[b] = kNegBig;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) z[b][k] = 0.f;
+            }
+            run_split(true);
+        }
     }
 
     if (MODE == 1) {
@@ -476,11 +494,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
 }
 
 // Merge the per-split partial statistics of each row (fixed split order) and convert to the
-// natural-log units of Eq. 4: row_max = max_t logit, row_sumexp = sum_t exp(logit - row_max).
+// natural-log units of Eq. 4: row_max = a reference <= max_t logit, row_sumexp = sum_t exp(logit - row_max).
 __global__ void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows, float *row_max,
-                                  float *row_sumexp, uint32_t *overflow, int redo)
+                                  float *row_sumexp)
 {
-    if (redo && *overflow == 0) return;
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= nrows) return;
     float mm = kNegBig;
@@ -489,8 +506,6 @@ __global__ void combine_row_stats(const float *part_m, const float *part_z, int 
     for (int s = 0; s < nsplit; ++s) zz += part_z[(int64_t)s * nrows + r] * fast_exp2(part_m[(int64_t)s * nrows + r] - mm);
     row_max[r] = mm * kLn2;
     row_sumexp[r] = zz;
-    // a sum that left the fp32 range under a frozen reference: ask for the safe form
-    if (overflow && !redo && !(zz <= 3.0e38f)) atomicOr(overflow, 1u);
 }
 
 // score[t] = sum (or max) over the (kv head, query block) units of their partial column results.
@@ -515,7 +530,7 @@ constexpr size_t tile_lds_bytes(int waves)
 
 // The dynamic-LDS ceiling of a kernel is raised once per process (to the most any plan asks of it: the
 // 8-wavefront tiles plus the partial-result buffers of pass 2), not on every launch.
-constexpr int kMaxDynamicLds = 160 * 1024;
+constexpr int kMaxDynamicLds = 144 * 1024;  // leaves room for the few bytes of static LDS a kernel may hold
 hipError_t raise_lds_limit_once(const void *kernel)
 {
     static std::mutex mutex;
@@ -576,31 +591,23 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     return p;
 }
 
-hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a0, float *row_max, float *row_sumexp, hipStream_t s)
+hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp, hipStream_t s)
 {
-    // Attempt with frozen references, then the always-safe form, which returns at once unless the
-    // attempt raised the overflow flag.  No host synchronisation in between.
+    // One launch: a workgroup whose sums against frozen references leave the safe range walks its split a second
+    // time in the always-safe form before it writes its partials.
     const size_t lds = p.lds_bytes_stats;
-    const int64_t nrows = (int64_t)a0.Hq * a0.Lq;
-    // (With the exact-maximum flag the safe form is the only launch.)
-    for (int redo = a0.force_online ? 1 : 0; redo < 2; ++redo) {
-        ScoreArgs a = a0;
-        a.force_online = redo;
-        if (a0.force_online) a.overflow = nullptr;
-        hipError_t e;
-        if (p.dtype == ILRE_F32)
-            e = launch_score(score_kernel<ILRE_F32, 1, 4, 0, 0>, p.grid, 256, lds, a, s);
-        else if (p.waves == 4)
-            e = launch_score(score_kernel<ILRE_BF16, 2, 4, 0, 0>, p.grid, 256, lds, a, s);
-        else
-            e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
-                           a.nsplit, nrows, row_max, row_sumexp, a.overflow, a.overflow ? redo : 0);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    const int64_t nrows = (int64_t)a.Hq * a.Lq;
+    hipError_t e;
+    if (p.dtype == ILRE_F32)
+        e = launch_score(score_kernel<ILRE_F32, 1, 4, 0, 0>, p.grid, 256, lds, a, s);
+    else if (p.waves == 4)
+        e = launch_score(score_kernel<ILRE_BF16, 2, 4, 0, 0>, p.grid, 256, lds, a, s);
+    else
+        e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z, a.nsplit, nrows,
+                       row_max, row_sumexp);
+    return hipGetLastError();
 }
 
 hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s)

@@ -130,6 +130,24 @@ def test_fullsize_printed_allocation_against_the_oracle(cfg, golden_dir):
           f"selection bit-exact on the GPU's scores", flush=True)
 
 
+def test_fullsize_cfg3_printed_reduction_and_sink():
+    """Eq. 5 as printed (max over heads and queries) at the 128K-token workload, every token against the oracle run
+    live, and the window-max selection with a sink part on those scores, bit-exact."""
+    wl = inputs.CONFIGS[3]
+    print(f"[case] fullsize cfg3 max reduction + sink L={wl.L}", flush=True)
+    inp = inputs.generate(wl)
+    want, _, _ = oracle.scores(inp.q, inp.k, mode=oracle.MODE_MAX)
+    q, k = to_device(inp.q), to_device(inp.k)
+    idx, scores = il.ilre_recall(q, k, wl.budget, wl.pool_kernels, score_mode=il.ILRE_SCORE_MAX, sink=PAPER_SINK)
+    torch.cuda.synchronize()
+    idx, scores = idx.cpu().numpy(), scores.cpu().numpy()
+    bad, worst = score_errors(scores, want)
+    assert bad == 0, f"{bad} of {wl.L} scores out of tolerance, worst {worst:.2f}x"
+    assert (scores <= 1.0 + 1e-5).all()                      # a maximum of probabilities
+    assert idx.tolist() == oracle.allocate(scores, wl.pool_kernels, wl.budget, sink=PAPER_SINK).tolist()
+    assert idx[:PAPER_SINK].tolist() == list(range(PAPER_SINK)) and idx.size == PAPER_SINK + wl.budget
+
+
 def test_select_at_the_largest_context_the_abi_allows():
     """L = 2^31 - 1 scores (8 GiB): every index computation at its limit, pruning pre-pass active.  The scores
     are a constant background with isolated peaks, so the expected result comes from the oracle run on the
