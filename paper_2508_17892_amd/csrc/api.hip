@@ -392,9 +392,10 @@ int ilre_select_max_avg(const float *scores, int64_t L, int32_t sink, int32_t bu
 
 namespace {
 
-// Eq. 4 and Eq. 5 into out_scores (the part the two forms of the whole path share).
+// Eq. 4 and Eq. 5 (the part the two forms of the whole path share).  The scores are left as per-unit partial
+// vectors, described by `fused`, for the selection to reduce into out_scores on its way.
 int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
-                float *out_scores, const ilre_opts *opts, const ilre::ScorePlan &p, const Layout &lay)
+                float *out_scores, const ilre_opts *opts, const ilre::ScorePlan &p, const Layout &lay, ilre::FusedScores &fused)
 {
     int rc;
     ilre::ScoreArgs a{};
@@ -413,8 +414,9 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     a.row_sumexp = row_sumexp;
     a.partial = (float *)(ws + lay.partial);
     a.dump = (float *)(ws + lay.flag) + 16;
-    e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s);
+    e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s, false);
     if (e != hipSuccess) return hip_fail(e, "column-score launch");
+    fused = ilre::FusedScores{a.partial, p.nunits, opts->score_mode == ILRE_SCORE_MAX ? 1 : 0, out_scores, L};
     return ILRE_OK;
 }
 
@@ -502,11 +504,12 @@ int ilre_recall(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     // workspace sized for the whole context (what ilre_workspace_bytes reports); the selection then runs on the body
     const Layout lay = make_layout(p, L, (int64_t)Hq * Lq, window_job(L, 0, budget, pool_kernels, opts->n_pool_kernels));
     if ((rc = check_workspace(opts, lay.total))) return rc;
-    if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay))) return rc;
+    ilre::FusedScores fused{};
+    if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay, fused))) return rc;
     unsigned char *ws = (unsigned char *)opts->workspace;
     const ilre::SelectJob job = window_job(L, opts->sink, budget, pool_kernels, opts->n_pool_kernels);
     const hipError_t e = ilre::launch_select(out_scores + opts->sink, job, out_idx, nullptr, ws + lay.select,
-                                             ilre::make_select_layout(job), (hipStream_t)opts->stream);
+                                             ilre::make_select_layout(job), (hipStream_t)opts->stream, &fused);
     if (e != hipSuccess) return hip_fail(e, "selection launch");
     return ILRE_OK;
 }
@@ -525,9 +528,11 @@ int ilre_recall_max_avg(const void *q, const void *k_cache, int64_t L, int32_t L
     const ilre::SelectJob job = max_avg_job(L, sink, budget, max_kernels, n_max, avg_kernels, n_avg);
     const Layout lay = make_layout(p, L, (int64_t)Hq * Lq, job);
     if ((rc = check_workspace(opts, lay.total))) return rc;
-    if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay))) return rc;
+    ilre::FusedScores fused{};
+    if ((rc = run_scoring(q, k_cache, L, Lq, Hq, Hkv, d, out_scores, opts, p, lay, fused))) return rc;
     unsigned char *ws = (unsigned char *)opts->workspace;
-    const hipError_t e = ilre::launch_select(out_scores + sink, job, out_idx, out_count, ws + lay.select, lay.sel, (hipStream_t)opts->stream);
+    const hipError_t e = ilre::launch_select(out_scores + sink, job, out_idx, out_count, ws + lay.select, lay.sel,
+                                             (hipStream_t)opts->stream, &fused);
     if (e != hipSuccess) return hip_fail(e, "selection launch");
     return ILRE_OK;
 }

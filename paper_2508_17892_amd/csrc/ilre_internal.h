@@ -55,8 +55,11 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv);
 
 hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp,
                             hipStream_t s);
+// reduce = false leaves the per-unit partial score vectors in a.partial for launch_reduce_units (or for the
+// selection's first pass, which can do the reduction on its way).
 hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores,
-                             hipStream_t s);
+                             hipStream_t s, bool reduce = true);
+hipError_t launch_reduce_units(const float *partial, int nunits, int64_t L, int rmax, float *out_scores, hipStream_t s);
 
 // ---------------------------------------------------------------- selection (Algorithm 1)
 
@@ -125,8 +128,19 @@ struct SelCtrl {
 // Workspace carving for a job (only mode, L, counts and the max kernels are read).
 SelectLayout make_select_layout(const SelectJob &job);
 
+// Scores that still lie as per-unit partial vectors (the whole path): the selection reduces them into
+// `scores` (all L positions, sink part included) itself, in its first pass where it can.
+struct FusedScores {
+    const float *partial;  // [nunits][L]
+    int nunits;
+    int rmax;              // 0 sum, 1 max over the units
+    float *scores;         // L floats
+    int64_t L;
+};
+
+// `scores` points at the body (the first token after the sink part).
 hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
-                         void *workspace, const SelectLayout &lay, hipStream_t s);
+                         void *workspace, const SelectLayout &lay, hipStream_t s, const FusedScores *fused = nullptr);
 
 hipError_t launch_gather_ids(const int32_t *ids, int64_t L, const int32_t *idx, int n, int32_t *out, hipStream_t s);
 

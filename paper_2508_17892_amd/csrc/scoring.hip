@@ -610,7 +610,17 @@ hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_m
     return hipGetLastError();
 }
 
-hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s)
+hipError_t launch_reduce_units(const float *partial, int nunits, int64_t L, int rmax, float *out_scores, hipStream_t s)
+{
+    const unsigned blocks = (unsigned)((L + 255) / 256);
+    if (rmax)
+        hipLaunchKernelGGL(reduce_units<1>, dim3(blocks), dim3(256), 0, s, partial, nunits, L, out_scores);
+    else
+        hipLaunchKernelGGL(reduce_units<0>, dim3(blocks), dim3(256), 0, s, partial, nunits, L, out_scores);
+    return hipGetLastError();
+}
+
+hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s, bool reduce)
 {
     hipError_t e;
     const size_t lds = p.lds_bytes_cols;
@@ -624,13 +634,8 @@ hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_m
     else
         e = mx ? launch_score(score_kernel<ILRE_BF16, 2, 8, 1, 1>, p.grid, 512, lds, a, s)
                : launch_score(score_kernel<ILRE_BF16, 2, 8, 1, 0>, p.grid, 512, lds, a, s);
-    if (e != hipSuccess) return e;
-    const unsigned blocks = (unsigned)((a.L + 255) / 256);
-    if (mx)
-        hipLaunchKernelGGL(reduce_units<1>, dim3(blocks), dim3(256), 0, s, a.partial, p.nunits, a.L, out_scores);
-    else
-        hipLaunchKernelGGL(reduce_units<0>, dim3(blocks), dim3(256), 0, s, a.partial, p.nunits, a.L, out_scores);
-    return hipGetLastError();
+    if (e != hipSuccess || !reduce) return e;
+    return launch_reduce_units(a.partial, p.nunits, a.L, mx ? 1 : 0, out_scores, s);
 }
 
 }  // namespace ilre

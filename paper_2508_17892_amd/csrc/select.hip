@@ -363,6 +363,69 @@ __device__ __forceinline__ void wave_append(bool pred, T item, T *list, uint32_t
     if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = item;
 }
 
+// Histogram accounting of a wavefront's kPerThread values per lane (element `first + lane + 64k`, valid while
+// below `len`) into the workgroup's LDS histogram.  LEVEL 1: key bits 31..21.  LEVEL 2: bits 20..10 of the
+// keys whose bits 31..21 equal bin1.
+template <int LEVEL>
+__device__ __forceinline__ void hist_account(uint32_t *lh, const float (&pooled)[kPerThread], int64_t first, int64_t len,
+                                             uint32_t bin1)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const int64_t el = first + lane + k * 64;
+        const uint32_t key = ordered_bits(pooled[k]);
+        if (LEVEL == 1) {
+            // Real score distributions put most of a wavefront's 64 keys into one or two bins, and
+            // same-address LDS atomics serialise: the two most common bins are counted with ballots
+            // and added once, whatever is left goes one by one.
+            const uint32_t bin = key >> 21;
+            bool todo = el >= 0 && el < len;
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const uint64_t open = __ballot(todo);
+                if (open == 0) break;  // uniform
+                const int leader = __ffsll((unsigned long long)open) - 1;
+                const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+                const uint64_t same = __ballot(todo && bin == b0);
+                if (lane == leader) atomicAdd(&lh[b0], (uint32_t)__popcll(same));
+                todo = todo && bin != b0;
+            }
+            if (todo) atomicAdd(&lh[bin], 1u);
+        } else if (el >= 0 && el < len && (key >> 21) == bin1) {
+            atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
+        }
+    }
+}
+
+// The workgroup's LDS histogram goes to the combination's global one; the last workgroup of combination j to
+// get here sees it complete and locates the bin.  The bins are only ever touched by device-scope atomics (adds
+// here, atomic loads in find_bins), which are performed at the memory side, common to all eight L2s.  Each
+// thread waits until its adds have been performed (vmcnt counts them), then one thread counts the workgroup in
+// with another device-scope atomic: whoever reads the final count reads, with atomic loads issued after it, bins
+// that hold every add.  A device-scope release fence in their place would also write this L2's unrelated dirty
+// lines back, tens of microseconds per workgroup; the acquire side, one workgroup per combination, is cheap and
+// is there.  `counter` is the completion counter of this level and combination, `workgroups` how many count in.
+template <int LEVEL>
+__device__ __forceinline__ void hist_finish(uint32_t *lh, uint32_t *hist, SelCtrl *ctrl, int j, uint32_t *counter,
+                                            uint32_t workgroups, uint32_t *is_last)
+{
+    __syncthreads();
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) {
+        const uint32_t c = lh[i];
+        if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *is_last = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == workgroups - 1;
+    __syncthreads();
+    if (*is_last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        find_bins<LEVEL>(hist, ctrl, j);
+    }
+}
+
 // LEVEL 1: histogram of key bits 31..21 over the visited elements.  LEVEL 2: of bits 20..10 over the
 // elements whose bits 31..21 equal the combination's level-1 bin.  grid = (workgroups, combinations);
 // the wavefronts of a grid row share out the entries.
@@ -375,7 +438,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int
     __shared__ uint32_t is_last;
     const int j = blockIdx.y;
     const Pooling pl = pooling_of(vals, ctrl[j]);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wave = threadIdx.x >> 6;
     uint32_t *hist = hist_all + (size_t)(LEVEL - 1) * n * kSelBins;
     float *b0 = (float *)smem + (size_t)wave * 2 * pool_lds_floats(pl.before, pl.after);
     float *b1 = b0 + pool_lds_floats(pl.before, pl.after);
@@ -383,33 +446,6 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int
     for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
     __syncthreads();
     const uint32_t nent = entry_count(ent, (uint32_t)pl.len);
-    auto account = [&](const float (&pooled)[kPerThread], int64_t fc) {
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            const int64_t el = fc * kSelFine + lane + k * 64;
-            const uint32_t key = ordered_bits(pooled[k]);
-            if (LEVEL == 1) {
-                // Real score distributions put most of a wavefront's 64 keys into one or two bins, and
-                // same-address LDS atomics serialise: the two most common bins are counted with ballots
-                // and added once, whatever is left goes one by one.
-                const uint32_t bin = key >> 21;
-                bool todo = el < pl.len;
-#pragma unroll
-                for (int r = 0; r < 2; ++r) {
-                    const uint64_t open = __ballot(todo);
-                    if (open == 0) break;  // uniform
-                    const int leader = __ffsll((unsigned long long)open) - 1;
-                    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
-                    const uint64_t same = __ballot(todo && bin == b0);
-                    if (lane == leader) atomicAdd(&lh[b0], (uint32_t)__popcll(same));
-                    todo = todo && bin != b0;
-                }
-                if (todo) atomicAdd(&lh[bin], 1u);
-            } else if (el < pl.len && (key >> 21) == bin1) {
-                atomicAdd(&lh[(key >> 10) & (kSelBins - 1)], 1u);
-            }
-        }
-    };
     if (raw_window(pl)) {
         // window 1: the elements themselves; a wavefront fetches kRawBatch fine chunks before it accounts for
         // any, so that their loads are in flight together
@@ -419,38 +455,84 @@ __global__ __launch_bounds__(kPoolThreads) void pool_hist(const float *vals, int
             raw_fetch(pl, ent, e0, nent, fcs, vals_);
 #pragma unroll
             for (int u = 0; u < kRawBatch; ++u)
-                if (fcs[u] >= 0) account(vals_[u], fcs[u]);  // uniform
+                if (fcs[u] >= 0) hist_account<LEVEL>(lh, vals_[u], fcs[u] * kSelFine, pl.len, bin1);  // uniform
         }
     } else {
         for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
             const int64_t fc = entry_chunk(ent, e);
             float pooled[kPerThread];
             pooled_wave(pl, fc, b0, b1, pooled);
-            account(pooled, fc);
+            hist_account<LEVEL>(lh, pooled, fc * kSelFine, pl.len, bin1);
         }
     }
+    hist_finish<LEVEL>(lh, hist, ctrl, j, &done[(LEVEL - 1) * n + j], gridDim.x, &is_last);
+}
+
+// The whole path's first selection pass, fused with the last scoring step: score[t] = sum (or max) over the
+// (kv head, query block) units of their partial column results, written out for every token, and the level-1
+// histogram of the body's scores (tokens sink .. L-1) for the single seed combination, in one pass over the
+// partial vectors.  The sum runs in unit order, as in the stand-alone reduction.
+template <int RMAX>
+__global__ __launch_bounds__(kPoolThreads) void reduce_hist1(const float *partial, int nunits, int64_t L, int sink, float *score,
+                                                             SelCtrl *ctrl, uint32_t *hist, uint32_t *done)
+{
+    __shared__ uint32_t lh[kSelBins];
+    __shared__ uint32_t is_last;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) lh[i] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) {
-        const uint32_t c = lh[i];
-        if (c) atomicAdd(&hist[(size_t)j * kSelBins + i], c);
+    const uint32_t nfine = (uint32_t)((L + kSelFine - 1) / kSelFine);
+    // A wavefront takes kChunks fine chunks a round and the units eight at a time: 64 independent loads per lane
+    // are in flight before the first sum (the partial vectors are 64 MiB at 1M tokens; this pass is their one
+    // reader and must run at memory speed).
+    constexpr int kChunks = 2, kUnits = 8;
+    for (uint32_t fc0 = (blockIdx.x * kPoolWaves + wave) * kChunks; fc0 < nfine; fc0 += gridDim.x * kPoolWaves * kChunks) {
+        float v[kChunks][kPerThread];
+        int64_t tok[kChunks][kPerThread];
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c)
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) {
+                const int64_t t = (int64_t)(fc0 + c) * kSelFine + lane + k * 64;
+                tok[c][k] = t < L ? t : L - 1;
+            }
+        for (int u0 = 0; u0 < nunits; u0 += kUnits) {
+            float x[kUnits][kChunks][kPerThread];
+#pragma unroll
+            for (int uu = 0; uu < kUnits; ++uu) {
+                const int64_t u = u0 + uu < nunits ? u0 + uu : nunits - 1;
+#pragma unroll
+                for (int c = 0; c < kChunks; ++c)
+#pragma unroll
+                    for (int k = 0; k < kPerThread; ++k) x[uu][c][k] = partial[u * L + tok[c][k]];
+            }
+#pragma unroll
+            for (int uu = 0; uu < kUnits; ++uu) {
+                if (u0 + uu >= nunits) break;  // uniform
+#pragma unroll
+                for (int c = 0; c < kChunks; ++c)
+#pragma unroll
+                    for (int k = 0; k < kPerThread; ++k) {
+                        if (u0 + uu == 0)
+                            v[c][k] = x[uu][c][k];
+                        else
+                            v[c][k] = RMAX ? fmaxf(v[c][k], x[uu][c][k]) : v[c][k] + x[uu][c][k];
+                    }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c) {
+            if (fc0 + c >= nfine) break;  // uniform
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) {
+                const int64_t t = (int64_t)(fc0 + c) * kSelFine + lane + k * 64;
+                if (t < L) score[t] = v[c][k];
+            }
+            // body element of token t is t - sink; the sink tokens (negative elements) are not counted
+            hist_account<1>(lh, v[c], (int64_t)(fc0 + c) * kSelFine - sink, L - sink, 0);
+        }
     }
-    // The last workgroup of combination j to get here sees its histogram complete and locates the bin.  The
-    // bins are only ever touched by device-scope atomics (adds here, atomic loads in find_bins), which are
-    // performed at the memory side, common to all eight L2s.  Each thread waits until its adds have been
-    // performed (vmcnt counts them), then one thread counts the workgroup in with another device-scope atomic:
-    // whoever reads the final count reads, with atomic loads issued after it, bins that hold every add.  A
-    // device-scope release fence in their place would also write this L2's unrelated dirty lines back, tens of
-    // microseconds per workgroup; the acquire side, one workgroup per combination, is cheap and is there.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0)
-        is_last = __hip_atomic_fetch_add(&done[(LEVEL - 1) * n + j], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                  gridDim.x - 1;
-    __syncthreads();
-    if (is_last) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        find_bins<LEVEL>(hist, ctrl, j);
-    }
+    hist_finish<1>(lh, hist, ctrl, 0, &done[0], gridDim.x, &is_last);
 }
 
 __global__ __launch_bounds__(kPoolThreads) void collect(const float *vals, SelCtrl *ctrl, uint64_t *cand, uint64_t *tie,
@@ -1111,7 +1193,7 @@ constexpr uint32_t kHistGrid = 2560, kCollectGrid = 8192;
 // Window-max form: the seeds (best raw scores), their ranks and neighbours, one ranked token list per
 // kernel size, the walk.
 hipError_t launch_select_window(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
-                                unsigned char *ws, const SelectLayout &lay, hipStream_t s)
+                                unsigned char *ws, const SelectLayout &lay, hipStream_t s, const FusedScores *fused)
 {
     const int64_t L = job.L;
     const int n = job.combos();
@@ -1158,7 +1240,13 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
     const size_t pool_lds = (size_t)kPoolWaves * 2 * (size_t)kSelFine * sizeof(float);
     Entries ent{nullptr, nullptr};
     uint32_t entries = nfine;
-    if ((int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384) {
+    const bool pruned = (int64_t)nfine >= 4 * (int64_t)n_out && nfine >= 16384;
+    if (fused && pruned) {  // the pre-pass wants the finished scores
+        const hipError_t e = launch_reduce_units(fused->partial, fused->nunits, fused->L, fused->rmax, fused->scores, s);
+        if (e != hipSuccess) return e;
+        fused = nullptr;
+    }
+    if (pruned) {
         // Long contexts: only fine chunks whose maximum reaches the n_out-th largest chunk maximum (up to its
         // 22-bit prefix) can hold one of the n_out best scores; visit only those.
         float *cm = (float *)(ws + lay.cmax);
@@ -1188,7 +1276,18 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
     const uint32_t batches = (entries + kRawBatch - 1) / kRawBatch;
     const uint32_t hblocks = pool_blocks(batches, 256u), cblocks = pool_blocks(batches, 1024u);
     hipLaunchKernelGGL(sel_init, dim3(1), dim3(kThreads), 0, s, prm, hist, ctrl, done);
-    hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
+    if (fused) {
+        // the last step of the scoring (sum of the partial score vectors) and the level-1 histogram in one pass
+        const uint32_t rblocks = pool_blocks((uint32_t)((fused->L + kSelFine - 1) / kSelFine + 1) / 2, 512u);
+        if (fused->rmax)
+            hipLaunchKernelGGL(reduce_hist1<1>, dim3(rblocks), dim3(kPoolThreads), 0, s, fused->partial, fused->nunits, fused->L,
+                               job.sink, fused->scores, ctrl, hist, done);
+        else
+            hipLaunchKernelGGL(reduce_hist1<0>, dim3(rblocks), dim3(kPoolThreads), 0, s, fused->partial, fused->nunits, fused->L,
+                               job.sink, fused->scores, ctrl, hist, done);
+    } else {
+        hipLaunchKernelGGL(pool_hist<1>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
+    }
     hipLaunchKernelGGL(pool_hist<2>, dim3(hblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, 1, ctrl, hist, done, ent);
     hipLaunchKernelGGL(collect, dim3(cblocks, 1), dim3(kPoolThreads), pool_lds, s, scores, ctrl, cand, tie, ent);
     hipLaunchKernelGGL(refine, dim3(1), dim3(kThreads), 0, s, ctrl, cand, tie, 0u);
@@ -1206,7 +1305,7 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
 }  // namespace
 
 hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out_idx, int32_t *out_count,
-                         void *workspace, const SelectLayout &lay, hipStream_t s)
+                         void *workspace, const SelectLayout &lay, hipStream_t s, const FusedScores *fused)
 {
     const int64_t L = job.L;
     const int n = job.combos();
@@ -1225,12 +1324,16 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
 
     hipError_t e = set_select_attributes();
     if (e != hipSuccess) return e;
+    if (fused && (job.mode != kSelWindowMax || L == 0)) {  // only the window-max form takes the scores unreduced
+        if ((e = launch_reduce_units(fused->partial, fused->nunits, fused->L, fused->rmax, fused->scores, s)) != hipSuccess) return e;
+        fused = nullptr;
+    }
     if (L == 0) {  // nothing but the sink part
         hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl, cand, 0, 0, picked, picked_n);
         hipLaunchKernelGGL(emit_sorted, emit_grid, dim3(kEmitThreads), 0, s, picked, picked_n, 0, job.sink, out_idx, out_count);
         return hipGetLastError();
     }
-    if (job.mode == kSelWindowMax) return launch_select_window(scores, job, out_idx, out_count, ws, lay, s);
+    if (job.mode == kSelWindowMax) return launch_select_window(scores, job, out_idx, out_count, ws, lay, s, fused);
 
     // The algorithm as printed.  B_c: floor(B / n), the first B mod n combinations one more; K_m = B / m + 1 cells.
     SelParams prm{};
