@@ -132,6 +132,18 @@ def run_workload(il, torch, np, inputs, cfg: int, steps: int, warmup: int, calib
         ev[i][3].record()
     torch.cuda.synchronize()
     stage_ms = [float(np.mean([ev[i][s].elapsed_time(ev[i][s + 1]) for i in range(steps)])) for s in range(3)]
+    # Device time of the whole step, HIP events around the same K calls.  What it takes beyond the two scoring
+    # passes is the selection as it runs inside a step: its launches queue up behind the long scoring kernels,
+    # while the stand-alone `select` stage above is bounded by how fast the host can enqueue nine small kernels;
+    # in the whole path the selection's first pass also does the sum of the partial score vectors that the staged
+    # col_scores figure includes.
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    r0.record()
+    for _ in range(steps):
+        step()
+    r1.record()
+    torch.cuda.synchronize()
+    recall_ms = r0.elapsed_time(r1) / steps
 
     flops_per_pass = 2.0 * wl.Hq * wl.Lq * wl.L * wl.d
     dom = 0 if stage_ms[0] >= stage_ms[1] else 1
@@ -157,7 +169,8 @@ def run_workload(il, torch, np, inputs, cfg: int, steps: int, warmup: int, calib
                    "pool_kernels": list(kernels), "budget": budget, "needle_spans": wl.n_spans,
                    "input_gen_s": round(gen_s, 1)},
         "stage_ms": {"row_stats": round(stage_ms[0], 4), "col_scores": round(stage_ms[1], 4),
-                     "select": round(stage_ms[2], 4)},
+                     "select": round(stage_ms[2], 4), "recall_device": round(recall_ms, 4),
+                     "after_scoring_in_recall": round(recall_ms - stage_ms[0] - stage_ms[1], 4)},
         "stage_tflops": {"row_stats": round(flops_per_pass / stage_ms[0] / 1e9, 1),
                          "col_scores": round(flops_per_pass / stage_ms[1] / 1e9, 1)},
         "roofline": roofline,
