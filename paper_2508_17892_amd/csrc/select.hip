@@ -626,22 +626,40 @@ __global__ __launch_bounds__(kPoolThreads) void chunk_max(const float *scores, i
 // chunk maximum): at least `budget` tokens score at or above the lower edge of that maximum's 22-bit
 // prefix, so no kernel admits a token whose pooled score is below it; a fine chunk can only hold such
 // a token if a chunk maximum within `reach` chunks of it reaches the prefix.
+// One slot reservation per workgroup (same-address atomics serialise at about 13 ns each, and a few thousand
+// scattered hits would otherwise mean a few thousand of them): a thread looks at kMarkPerThread consecutive chunks.
+constexpr int kMarkPerThread = 16;
 __global__ __launch_bounds__(kPoolThreads) void mark_active(const float *cm, uint32_t nfine, int reach, SelCtrl *pctrl,
                                                             uint32_t *list)
 {
-    const uint32_t c = blockIdx.x * kPoolThreads + threadIdx.x;
+    __shared__ uint32_t wsum[kPoolWaves];
+    __shared__ uint32_t base_slot;
+    const uint32_t c0 = (blockIdx.x * kPoolThreads + threadIdx.x) * kMarkPerThread;
     const uint32_t bin1 = pctrl->bin1, bin2 = pctrl->bin2;
     const uint32_t prefix = (bin1 >= (uint32_t)kSelBins || bin2 >= (uint32_t)kSelBins) ? 0u : (bin1 << 11) | bin2;
-    bool active = false;
-    if (c < nfine) {
-        float m = cm[c];
-        for (int d = 1; d <= reach; ++d) {
-            if (c >= (uint32_t)d) m = fmaxf(m, cm[c - d]);
-            if (c + d < nfine) m = fmaxf(m, cm[c + d]);
+    uint32_t hits = 0;  // bit i: chunk c0 + i is active
+#pragma unroll
+    for (int i = 0; i < kMarkPerThread; ++i) {
+        const uint32_t c = c0 + i;
+        if (c < nfine) {
+            float m = cm[c];
+            for (int d = 1; d <= reach; ++d) {
+                if (c >= (uint32_t)d) m = fmaxf(m, cm[c - d]);
+                if (c + d < nfine) m = fmaxf(m, cm[c + d]);
+            }
+            if ((ordered_bits(m) >> 10) >= prefix) hits |= 1u << i;
         }
-        active = (ordered_bits(m) >> 10) >= prefix;
     }
-    wave_append(active, c, list, &pctrl->cand_n);
+    uint32_t total;
+    const uint32_t mine = (uint32_t)__popc(hits);
+    uint32_t at = block_scan_inclusive<kPoolThreads>(mine, wsum, total) - mine;
+    if (total == 0) return;  // uniform
+    if (threadIdx.x == 0) base_slot = atomicAdd(&pctrl->cand_n, total);
+    __syncthreads();
+    at += base_slot;
+#pragma unroll
+    for (int i = 0; i < kMarkPerThread; ++i)
+        if ((hits >> i) & 1u) list[at++] = c0 + i;
 }
 
 // Boundary list -> candidates.  Window-max form: short lists (the normal case) are appended whole,
@@ -1266,7 +1284,8 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
         const uint32_t pblocks = pool_blocks((nfine2 + kRawBatch - 1) / kRawBatch, 1024);
         hipLaunchKernelGGL(pool_hist<1>, dim3(pblocks, 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
         hipLaunchKernelGGL(pool_hist<2>, dim3(pblocks, 1), dim3(kPoolThreads), pool_lds, s, cm, 1, pctrl, phist, pdone, all);
-        hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads - 1) / kPoolThreads), dim3(kPoolThreads), 0, s, cm, nfine, 0, pctrl, active);
+        hipLaunchKernelGGL(mark_active, dim3((nfine + kPoolThreads * kMarkPerThread - 1) / (kPoolThreads * kMarkPerThread)), dim3(kPoolThreads), 0, s, cm,
+                           nfine, 0, pctrl, active);
         ent = Entries{active, &pctrl->cand_n};
         // with a list the entry count is only known on the device: size the grid for the worst case the
         // pruning rule is meant for (a few times the budget) and let the wavefronts loop
