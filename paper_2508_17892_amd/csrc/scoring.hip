@@ -500,10 +500,30 @@ __global__ void combine_row_stats(const float *part_m, const float *part_z, int 
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= nrows) return;
+    // eight splits at a time, their loads issued together (one load per dependent step would make this tiny
+    // kernel a chain of memory latencies)
+    constexpr int kBlock = 8;
     float mm = kNegBig;
-    for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, part_m[(int64_t)s * nrows + r]);
+    for (int s0 = 0; s0 < nsplit; s0 += kBlock) {
+        float m[kBlock];
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) m[i] = part_m[(int64_t)(s0 + i < nsplit ? s0 + i : nsplit - 1) * nrows + r];
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) mm = fmaxf(mm, m[i]);
+    }
     float zz = 0.f;
-    for (int s = 0; s < nsplit; ++s) zz += part_z[(int64_t)s * nrows + r] * fast_exp2(part_m[(int64_t)s * nrows + r] - mm);
+    for (int s0 = 0; s0 < nsplit; s0 += kBlock) {
+        float m[kBlock], z[kBlock];
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) {
+            const int64_t at = (int64_t)(s0 + i < nsplit ? s0 + i : nsplit - 1) * nrows + r;
+            m[i] = part_m[at];
+            z[i] = part_z[at];
+        }
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i)
+            if (s0 + i < nsplit) zz += z[i] * fast_exp2(m[i] - mm);  // split order, as before
+    }
     row_max[r] = mm * kLn2;
     row_sumexp[r] = zz;
 }
@@ -514,10 +534,21 @@ __global__ void reduce_units(const float *partial, int nunits, int64_t L, float 
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= L) return;
-    float acc = partial[t];
-    for (int u = 1; u < nunits; ++u) {
-        const float x = partial[(int64_t)u * L + t];
-        acc = RMAX ? fmaxf(acc, x) : acc + x;
+    // eight units at a time, their loads issued together; the sum runs in unit order
+    constexpr int kBlock = 8;
+    float acc = 0.f;
+    for (int u0 = 0; u0 < nunits; u0 += kBlock) {
+        float x[kBlock];
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) x[i] = partial[(int64_t)(u0 + i < nunits ? u0 + i : nunits - 1) * L + t];
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) {
+            if (u0 + i >= nunits) break;
+            if (u0 + i == 0)
+                acc = x[i];
+            else
+                acc = RMAX ? fmaxf(acc, x[i]) : acc + x[i];
+        }
     }
     score[t] = acc;
 }
