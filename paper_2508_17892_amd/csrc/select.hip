@@ -129,6 +129,26 @@ __device__ __forceinline__ uint32_t wave_total(uint32_t scanned)  // lane 63 of 
 {
     return (uint32_t)__builtin_amdgcn_readlane((int)scanned, 63);
 }
+// Copy n items from global memory into LDS with the whole block, eight loads in flight per thread.
+template <typename T, int THREADS>
+__device__ __forceinline__ void stage_to_lds(T *dst, const T *src, uint32_t n)
+{
+    constexpr int kBatch = 8;
+    for (uint32_t i0 = threadIdx.x; i0 < n; i0 += THREADS * kBatch) {
+        T x[kBatch];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const uint32_t i = i0 + b * THREADS;
+            x[b] = src[i < n ? i : n - 1];
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const uint32_t i = i0 + b * THREADS;
+            if (i < n) dst[i] = x[b];
+        }
+    }
+}
+
 // Inclusive prefix sum over the THREADS threads of the block; wsum is THREADS / 64 words of LDS
 // scratch.  Every thread also receives the block total.  Contains two barriers.
 template <int THREADS>
@@ -809,7 +829,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted(const uint32_t *pick
     for (uint32_t i = nsel + gtid; i < (uint32_t)n_out; i += gsize) out_idx[sink + i] = -1;
     if (gtid == 0 && out_count) *out_count = sink + (int32_t)nsel;
     if (blockIdx.x * (kEmitThreads / 16) >= nsel) return;  // uniform
-    for (uint32_t i = threadIdx.x; i < nsel; i += kEmitThreads) all[i] = picked[i];
+    stage_to_lds<uint32_t, kEmitThreads>(all, picked, nsel);
     __syncthreads();
     const uint32_t i = blockIdx.x * (kEmitThreads / 16) + (threadIdx.x >> 4);
     const int sub = threadIdx.x & 15;
@@ -993,7 +1013,7 @@ __global__ __launch_bounds__(kSeedRankThreads) void seed_rank(const float *score
     const uint32_t ns = sc->total_n;
     if (blockIdx.x * (kSeedRankThreads / 16) >= ns) return;  // uniform
     // (the seeds were written by earlier kernels: plain loads, all in flight together)
-    for (uint32_t i = threadIdx.x; i < ns; i += kSeedRankThreads) all[i] = seeds[i];
+    stage_to_lds<uint64_t, kSeedRankThreads>(all, seeds, ns);
     __syncthreads();
     const uint32_t u = blockIdx.x * (kSeedRankThreads / 16) + (threadIdx.x >> 4);
     const int sub = threadIdx.x & 15;
