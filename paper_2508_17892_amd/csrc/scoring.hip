@@ -493,39 +493,53 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     }
 }
 
-// Merge the per-split partial statistics of each row (fixed split order) and convert to the
-// natural-log units of Eq. 4: row_max = a reference <= max_t logit, row_sumexp = sum_t exp(logit - row_max).
-__global__ void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows, float *row_max,
-                                  float *row_sumexp)
+// Merge the per-split partial statistics of each row (fixed order) and convert to the natural-log units of
+// Eq. 4: row_max = a reference <= max_t logit, row_sumexp = sum_t exp(logit - row_max).
+// Sixteen lanes share a row and the splits among them, so that all of a row's partials are fetched in one
+// round of loads (a thread a row would fetch them in a chain of memory latencies: this kernel sits between
+// the two scoring passes and is all latency).
+constexpr int kCombineLanes = 16;
+__global__ __launch_bounds__(256) void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows,
+                                                         float *row_max, float *row_sumexp)
 {
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= nrows) return;
-    // eight splits at a time, their loads issued together (one load per dependent step would make this tiny
-    // kernel a chain of memory latencies)
-    constexpr int kBlock = 8;
+    constexpr int kBlock = 4;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r = gid / kCombineLanes;
+    const int sub = (int)(gid % kCombineLanes);
+    const int64_t rr = r < nrows ? r : nrows - 1;  // surplus groups redo the last row and store nothing
     float mm = kNegBig;
-    for (int s0 = 0; s0 < nsplit; s0 += kBlock) {
+    for (int s0 = sub; s0 < nsplit; s0 += kCombineLanes * kBlock) {
         float m[kBlock];
 #pragma unroll
-        for (int i = 0; i < kBlock; ++i) m[i] = part_m[(int64_t)(s0 + i < nsplit ? s0 + i : nsplit - 1) * nrows + r];
+        for (int i = 0; i < kBlock; ++i) {
+            const int s = s0 + i * kCombineLanes;
+            m[i] = part_m[(int64_t)(s < nsplit ? s : nsplit - 1) * nrows + rr];
+        }
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) mm = fmaxf(mm, m[i]);
     }
+#pragma unroll
+    for (int o = 1; o < kCombineLanes; o <<= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
     float zz = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += kBlock) {
+    for (int s0 = sub; s0 < nsplit; s0 += kCombineLanes * kBlock) {
         float m[kBlock], z[kBlock];
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) {
-            const int64_t at = (int64_t)(s0 + i < nsplit ? s0 + i : nsplit - 1) * nrows + r;
+            const int s = s0 + i * kCombineLanes;
+            const int64_t at = (int64_t)(s < nsplit ? s : nsplit - 1) * nrows + rr;
             m[i] = part_m[at];
             z[i] = part_z[at];
         }
 #pragma unroll
         for (int i = 0; i < kBlock; ++i)
-            if (s0 + i < nsplit) zz += z[i] * fast_exp2(m[i] - mm);  // split order, as before
+            if (s0 + i * kCombineLanes < nsplit) zz += z[i] * fast_exp2(m[i] - mm);
     }
-    row_max[r] = mm * kLn2;
-    row_sumexp[r] = zz;
+#pragma unroll
+    for (int o = 1; o < kCombineLanes; o <<= 1) zz += __shfl_xor(zz, o);
+    if (sub == 0 && r < nrows) {
+        row_max[r] = mm * kLn2;
+        row_sumexp[r] = zz;
+    }
 }
 
 // score[t] = sum (or max) over the (kv head, query block) units of their partial column results.
@@ -636,8 +650,8 @@ hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_m
     else
         e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z, a.nsplit, nrows,
-                       row_max, row_sumexp);
+    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows * kCombineLanes + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
+                       a.nsplit, nrows, row_max, row_sumexp);
     return hipGetLastError();
 }
 

@@ -383,6 +383,39 @@ __device__ __forceinline__ void wave_append(bool pred, T item, T *list, uint32_t
     if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = item;
 }
 
+// The same for N items a lane (item g of every lane forms group g) and two lists at once: one slot reservation
+// per list for the whole lot, both in flight together.  A reservation is a returning atomic on one address, a
+// round trip to the memory side; one per group would chain N of them.
+template <int N>
+__device__ __forceinline__ void wave_append2(const bool (&pa)[N], const bool (&pb)[N], const uint64_t (&item)[N], uint64_t *la,
+                                             uint32_t *ca, uint64_t *lb, uint32_t *cb)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t na = 0, nb = 0;
+#pragma unroll
+    for (int g = 0; g < N; ++g) {
+        na += (uint32_t)__popcll(__ballot(pa[g]));
+        nb += (uint32_t)__popcll(__ballot(pb[g]));
+    }
+    if (na + nb == 0) return;  // uniform
+    uint32_t base_a = 0, base_b = 0;
+    if (lane == 0) {
+        base_a = atomicAdd(ca, na);
+        base_b = atomicAdd(cb, nb);
+    }
+    base_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)base_a);
+    base_b = (uint32_t)__builtin_amdgcn_readfirstlane((int)base_b);
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int g = 0; g < N; ++g) {
+        const uint64_t ma = __ballot(pa[g]), mb = __ballot(pb[g]);
+        if (pa[g]) la[base_a + (uint32_t)__popcll(ma & below)] = item[g];
+        if (pb[g]) lb[base_b + (uint32_t)__popcll(mb & below)] = item[g];
+        base_a += (uint32_t)__popcll(ma);
+        base_b += (uint32_t)__popcll(mb);
+    }
+}
+
 // Histogram accounting of a wavefront's kPerThread values per lane (element `first + lane + 64k`, valid while
 // below `len`) into the workgroup's LDS histogram.  LEVEL 1: key bits 31..21.  LEVEL 2: bits 20..10 of the
 // keys whose bits 31..21 equal bin1.
@@ -570,32 +603,39 @@ __global__ __launch_bounds__(kPoolThreads) void collect(const float *vals, SelCt
     uint64_t *cand_j = cand + (size_t)j * kCandCap;
     uint64_t *tie_j = tie + ctrl[j].tie_off;
     const uint32_t nent = entry_count(ent, (uint32_t)pl.len);
-    auto sort_out = [&](const float (&pooled)[kPerThread], int64_t fc) {
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            const int64_t el = fc * kSelFine + lane + k * 64;
-            const bool valid = el < pl.len;
-            const uint32_t p22 = valid ? ordered_bits(pooled[k]) >> 10 : 0;
-            const uint64_t key = make_key(pooled[k], (uint32_t)el);
-            wave_append(valid && p22 > prefix, key, cand_j, &ctrl[j].cand_n);
-            wave_append(valid && p22 == prefix, key, tie_j, &ctrl[j].tie_n);
-        }
+    // keys above the prefix are candidates, keys that share it go to the boundary list
+    auto classify = [&](float pooled, int64_t fc, int k, bool &above, bool &same, uint64_t &key) {
+        const int64_t el = fc * kSelFine + lane + k * 64;
+        const bool valid = fc >= 0 && el < pl.len;
+        const uint32_t p22 = valid ? ordered_bits(pooled) >> 10 : 0;
+        key = make_key(pooled, (uint32_t)el);
+        above = valid && p22 > prefix;
+        same = valid && p22 == prefix;
     };
     if (raw_window(pl)) {
         for (uint32_t e0 = (blockIdx.x * kPoolWaves + wave) * kRawBatch; e0 < nent; e0 += gridDim.x * kPoolWaves * kRawBatch) {
             float vals_[kRawBatch][kPerThread];
             int64_t fcs[kRawBatch];
             raw_fetch(pl, ent, e0, nent, fcs, vals_);
+            bool above[kRawBatch * kPerThread], same[kRawBatch * kPerThread];
+            uint64_t key[kRawBatch * kPerThread];
 #pragma unroll
             for (int u = 0; u < kRawBatch; ++u)
-                if (fcs[u] >= 0) sort_out(vals_[u], fcs[u]);  // uniform
+#pragma unroll
+                for (int k = 0; k < kPerThread; ++k)
+                    classify(vals_[u][k], fcs[u], k, above[u * kPerThread + k], same[u * kPerThread + k], key[u * kPerThread + k]);
+            wave_append2<kRawBatch * kPerThread>(above, same, key, cand_j, &ctrl[j].cand_n, tie_j, &ctrl[j].tie_n);
         }
     } else {
         for (uint32_t e = blockIdx.x * kPoolWaves + wave; e < nent; e += gridDim.x * kPoolWaves) {
             const int64_t fc = entry_chunk(ent, e);
             float pooled[kPerThread];
             pooled_wave(pl, fc, b0, b1, pooled);
-            sort_out(pooled, fc);
+            bool above[kPerThread], same[kPerThread];
+            uint64_t key[kPerThread];
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) classify(pooled[k], fc, k, above[k], same[k], key[k]);
+            wave_append2<kPerThread>(above, same, key, cand_j, &ctrl[j].cand_n, tie_j, &ctrl[j].tie_n);
         }
     }
 }
