@@ -151,9 +151,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     constexpr int TBLOCKS = TN / 32;
     constexpr int UNITS = TBLOCKS;              // pipeline units per tile: one per 32-token block
     constexpr int NPART = WAVES * 2;            // partial column results per token (pass 2)
-    constexpr int RSTR = TN + 36;               // row pitch of the partial-result buffers: keeps the two
-                                                // half-waves' stores and the flush's four lane groups on
-                                                // different LDS banks
+    // Row pitch of the partial-result buffers.  The flush reads them with four lanes per token, lane group g
+    // taking partials g*NPART/4 ..: the four groups of a half-wave must start 8 banks apart (8 tokens each)
+    // to cover the 32 LDS banks once.  The stores (32 consecutive tokens of one partial) never conflict.
+    constexpr int RSTR = TN + (NPART == 16 ? 34 : 36);
+    static_assert((NPART / 4 * RSTR) % 32 == 8 || (NPART / 4 * RSTR) % 32 == 24, "flush lane groups 8 banks apart");
     static_assert(TN * CPR % (64 * WAVES) == 0, "tile must divide over the wavefronts");
     static_assert(UNITS % 2 == 0, "units alternate between two accumulators");
     static_assert(TN == 16 * WAVES && NPART % 4 == 0, "column flush: 16 tokens per wavefront, 4 lanes per token");
@@ -632,7 +634,7 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     p.grid = (int)(((pairs + kNumXCD - 1) / kNumXCD) * kNumXCD * p.nqb);
     const size_t tiles = dtype == ILRE_F32 ? tile_lds_bytes<ILRE_F32>(p.waves) : tile_lds_bytes<ILRE_BF16>(p.waves);
     p.lds_bytes_stats = tiles;
-    p.lds_bytes_cols = tiles + 3 * 2 * (size_t)p.waves * (p.tile_tokens + 36) * sizeof(float);
+    p.lds_bytes_cols = tiles + 3 * 2 * (size_t)p.waves * (p.tile_tokens + 36) * sizeof(float);  // pitch <= tokens + 36
     return p;
 }
 

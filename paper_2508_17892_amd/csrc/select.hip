@@ -856,33 +856,49 @@ __device__ __forceinline__ void mark_allocated(uint32_t *table, uint32_t token)
 
 // Last step of the allocation: the sink indices, then the nsel allocated tokens in ascending order, then -1
 // up to sink + n_out.  The walk leaves the tokens in the order it took them; here every token counts the
-// tokens below it (16 lanes a token, the list staged in LDS), which is its place in the output whatever
-// order they arrived in and however they cluster.
-constexpr int kEmitThreads = 512;  // 32 tokens a workgroup
+// tokens below it, which is its place in the output whatever order they arrived in and however they
+// cluster.  The list is staged in LDS; a wavefront owns kEmitPerWave tokens and its lanes read disjoint
+// quarters of the list (every LDS word is fetched once per wavefront) and compare them with all of the
+// wavefront's tokens.
+constexpr int kEmitThreads = 512;
+constexpr int kEmitPerWave = 4;
+constexpr int kEmitPerBlock = kEmitThreads / 64 * kEmitPerWave;  // 32 tokens a workgroup
 __global__ __launch_bounds__(kEmitThreads) void emit_sorted(const uint32_t *picked, const uint32_t *picked_n, int n_out, int sink,
                                                             int32_t *out_idx, int32_t *out_count)
 {
-    __shared__ uint32_t all[ILRE_MAX_BUDGET];
+    __shared__ __align__(16) uint32_t all[ILRE_MAX_BUDGET];
+    static_assert(ILRE_MAX_BUDGET % 256 == 0, "the staged list is padded to whole rounds of 64 lanes x 4 tokens");
     const uint32_t nsel = *picked_n;
     const uint32_t gtid = blockIdx.x * kEmitThreads + threadIdx.x, gsize = gridDim.x * kEmitThreads;
     for (uint32_t i = gtid; i < (uint32_t)sink; i += gsize) out_idx[i] = (int32_t)i;
     for (uint32_t i = nsel + gtid; i < (uint32_t)n_out; i += gsize) out_idx[sink + i] = -1;
     if (gtid == 0 && out_count) *out_count = sink + (int32_t)nsel;
-    if (blockIdx.x * (kEmitThreads / 16) >= nsel) return;  // uniform
+    if (blockIdx.x * kEmitPerBlock >= nsel) return;  // uniform
     stage_to_lds<uint32_t, kEmitThreads>(all, picked, nsel);
+    const uint32_t padded = (nsel + 255u) & ~255u;  // the padding holds tokens no token is below
+    if (threadIdx.x < 256 && nsel + threadIdx.x < padded) all[nsel + threadIdx.x] = 0xFFFFFFFFu;
     __syncthreads();
-    const uint32_t i = blockIdx.x * (kEmitThreads / 16) + (threadIdx.x >> 4);
-    const int sub = threadIdx.x & 15;
-    if (i >= nsel) return;  // whole 16-lane groups leave together, no barrier follows
-    const uint32_t t = all[i];
-    uint32_t below = 0;
-#pragma unroll 8
-    for (uint32_t v = sub; v < nsel; v += 16) below += all[v] < t ? 1u : 0u;
-    below += (uint32_t)ILRE_DPP(0, below, 0x111, 0xF);
-    below += (uint32_t)ILRE_DPP(0, below, 0x112, 0xF);
-    below += (uint32_t)ILRE_DPP(0, below, 0x114, 0xF);
-    below += (uint32_t)ILRE_DPP(0, below, 0x118, 0xF);  // lane 15 of the row holds the total
-    if (sub == 15) out_idx[sink + below] = (int32_t)(t + (uint32_t)sink);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t i0 = blockIdx.x * kEmitPerBlock + wave * kEmitPerWave;
+    if (i0 >= nsel) return;  // whole wavefronts leave together, no barrier follows
+    uint32_t t[kEmitPerWave], below[kEmitPerWave];
+#pragma unroll
+    for (int q = 0; q < kEmitPerWave; ++q) {
+        t[q] = (uint32_t)__builtin_amdgcn_readfirstlane((int)all[i0 + q < nsel ? i0 + q : nsel - 1]);
+        below[q] = 0;
+    }
+#pragma unroll 2
+    for (uint32_t v = 4u * lane; v < padded; v += 256) {
+        const uint4 x = *(const uint4 *)&all[v];
+#pragma unroll
+        for (int q = 0; q < kEmitPerWave; ++q)
+            below[q] += (x.x < t[q] ? 1u : 0u) + (x.y < t[q] ? 1u : 0u) + (x.z < t[q] ? 1u : 0u) + (x.w < t[q] ? 1u : 0u);
+    }
+#pragma unroll
+    for (int q = 0; q < kEmitPerWave; ++q) {
+        const uint32_t place = wave_total(wave_scan_add(below[q]));
+        if (lane == q && i0 + q < nsel) out_idx[sink + place] = (int32_t)(t[q] + (uint32_t)sink);
+    }
 }
 
 // LDS writes of this wavefront done, then the workgroup barrier; global loads in flight stay in flight.
@@ -1042,8 +1058,9 @@ __global__ __launch_bounds__(kRankThreads) void allocate_ranked(const SelCtrl *c
 
 // Per seed u (one of the ns best raw scores, keys distinct): rank[u] = number of seeds with a larger key,
 // and the nearest token on either side, within `reach` tokens, whose key is larger (-1 / -1 if none; such a
-// token is itself a seed, the seeds being the best keys).  16 lanes share a seed: they split the other
-// seeds for the count and the neighbourhood for the scan.
+// token is itself a seed, the seeds being the best keys).  A wavefront owns four seeds.  For the count its
+// lanes read disjoint parts of the staged key list (every LDS word is fetched once per wavefront) and
+// compare them with all four keys; for the scan 16 lanes share a seed and split its neighbourhood.
 constexpr int kSeedRankThreads = 512;  // 32 seeds a workgroup
 __global__ __launch_bounds__(kSeedRankThreads) void seed_rank(const float *scores, int64_t L, const SelCtrl *sc, const uint64_t *seeds,
                                                               int reach, uint32_t *rank, int32_t *dom_left, int32_t *dom_right)
@@ -1054,18 +1071,37 @@ __global__ __launch_bounds__(kSeedRankThreads) void seed_rank(const float *score
     if (blockIdx.x * (kSeedRankThreads / 16) >= ns) return;  // uniform
     // (the seeds were written by earlier kernels: plain loads, all in flight together)
     stage_to_lds<uint64_t, kSeedRankThreads>(all, seeds, ns);
+    const uint32_t padded = (ns + 127u) & ~127u;  // whole rounds of 64 lanes x 2 keys; the padding outranks nothing
+    if (threadIdx.x < 128 && ns + threadIdx.x < padded) all[ns + threadIdx.x] = 0ull;
     __syncthreads();
-    const uint32_t u = blockIdx.x * (kSeedRankThreads / 16) + (threadIdx.x >> 4);
-    const int sub = threadIdx.x & 15;
-    if (u >= ns) return;  // whole 16-lane groups leave together, no barrier follows
-    const uint64_t key = all[u];
-    uint32_t cnt = 0;
-#pragma unroll 8
-    for (uint32_t v = sub; v < ns; v += 16) cnt += all[v] > key ? 1u : 0u;
-    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x111, 0xF);
-    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x112, 0xF);
-    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x114, 0xF);
-    cnt += (uint32_t)ILRE_DPP(0, cnt, 0x118, 0xF);  // lane 15 of the row holds the total
+    const int lane = threadIdx.x & 63;
+    const uint32_t u0 = blockIdx.x * (kSeedRankThreads / 16) + (threadIdx.x >> 6) * 4;  // the wavefront's first seed
+    if (u0 >= ns) return;  // whole wavefronts leave together, no barrier follows
+    uint64_t wkey[4];
+    uint32_t wcnt[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint64_t k = all[u0 + q < ns ? u0 + q : ns - 1];
+        wkey[q] = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(k >> 32)) << 32) |
+                  (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)k);
+        wcnt[q] = 0;
+    }
+#pragma unroll 2
+    for (uint32_t v = 2u * lane; v < padded; v += 128) {
+        const uint4 x = *(const uint4 *)&all[v];
+        const uint64_t k0 = ((uint64_t)x.y << 32) | x.x, k1 = ((uint64_t)x.w << 32) | x.z;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) wcnt[q] += (k0 > wkey[q] ? 1u : 0u) + (k1 > wkey[q] ? 1u : 0u);
+    }
+    uint32_t wtot[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) wtot[q] = wave_total(wave_scan_add(wcnt[q]));
+    const int grp = lane >> 4;
+    const uint32_t u = u0 + grp;
+    const int sub = lane & 15;
+    if (u >= ns) return;  // whole 16-lane groups leave together
+    const uint64_t key = grp == 0 ? wkey[0] : (grp == 1 ? wkey[1] : (grp == 2 ? wkey[2] : wkey[3]));
+    const uint32_t cnt = grp == 0 ? wtot[0] : (grp == 1 ? wtot[1] : (grp == 2 ? wtot[2] : wtot[3]));
     const int64_t pos = (int64_t)key_token(key);
     // nearest outranking token: distance d = 1 .. reach, 16 distances a round, both sides at once
     int32_t left = -1, right = -1;
@@ -1285,7 +1321,7 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
     int32_t *dom_left = (int32_t *)(rank + kCandCap), *dom_right = dom_left + kCandCap;
     const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
     uint32_t *picked = (uint32_t *)(ws + lay.picked), *picked_n = picked + ILRE_MAX_BUDGET;
-    const dim3 emit_grid((unsigned)((n_out + kEmitThreads / 16 - 1) / (kEmitThreads / 16)) + 1u);
+    const dim3 emit_grid((unsigned)((n_out + kEmitPerBlock - 1) / kEmitPerBlock) + 1u);
 
     // the seed combination: window 1 on the scores, the n_out best wanted
     SelParams prm{};
@@ -1373,7 +1409,7 @@ hipError_t launch_select_window(const float *scores, const SelectJob &job, int32
     // at most n_out + kSelSmall <= kCandCap seeds
     const uint32_t max_seeds = (uint32_t)n_out + (uint32_t)kSelSmall;
     hipLaunchKernelGGL(seed_rank, dim3((max_seeds + kSeedRankThreads / 16 - 1) / (kSeedRankThreads / 16)), dim3(kSeedRankThreads),
-                       (size_t)max_seeds * sizeof(uint64_t), s, scores, L, ctrl, cand, 2 * r_max, rank, dom_left, dom_right);
+                       (size_t)((max_seeds + 127u) & ~127u) * sizeof(uint64_t), s, scores, L, ctrl, cand, 2 * r_max, rank, dom_left, dom_right);
     hipLaunchKernelGGL(seed_lists, dim3(n), dim3(kThreads), 2 * (size_t)kCandCap * sizeof(uint32_t), s, sp, L, ctrl, cand, rank,
                        dom_left, dom_right, ctrl + 2, cand);
     hipLaunchKernelGGL(allocate_ranked, dim3(1), dim3(kRankThreads), alloc_lds, s, ctrl + 2, cand + kCandCap, n, n_out, picked, picked_n);
@@ -1399,7 +1435,7 @@ hipError_t launch_select(const float *scores, const SelectJob &job, int32_t *out
     float *cells = (float *)(ws + lay.cells);
     const size_t alloc_lds = (size_t)kHashSlots * sizeof(uint32_t) + (size_t)ILRE_MAX_BUDGET * sizeof(uint32_t);
     uint32_t *picked = (uint32_t *)(ws + lay.picked), *picked_n = picked + ILRE_MAX_BUDGET;
-    const dim3 emit_grid((unsigned)((n_out + kEmitThreads / 16 - 1) / (kEmitThreads / 16)) + 1u);
+    const dim3 emit_grid((unsigned)((n_out + kEmitPerBlock - 1) / kEmitPerBlock) + 1u);
 
     hipError_t e = set_select_attributes();
     if (e != hipSuccess) return e;
