@@ -115,6 +115,9 @@ SELECT_CASES = [
     ("twelve_kernels_two_groups", 30000, (1, 3, 5, 7, 9, 11, 13, 15, 31, 63, 127, 3), 3000, "needles"),
     ("all_equal_large", 300000, (3, 7, 15, 31), 4096, "equal"),
     ("two_values_heavy_ties", 150000, (1, 7), 5000, "two_values"),
+    # a later list whose best tokens are all taken: the walk has to go past its first stretch of ranks
+    ("repeated_kernel_sizes", 60000, (7, 7, 7, 7), 2000, "random"),
+    ("small_after_large", 80000, (63, 3, 1), 3000, "needles"),
     # long contexts: the pruning pre-pass (fine-chunk maxima) decides which chunks are visited
     ("pruned_needles", 5000000, (1, 3, 7, 15, 31), 4096, "needles"),
     ("pruned_dense_background", 4500001, (3, 31), 1000, "narrow"),
