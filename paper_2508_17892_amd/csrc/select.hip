@@ -39,9 +39,9 @@
 //   sel_init, pool_hist<1>, pool_hist<2>, collect, refine    as above, for ONE combination with window 1:
 //                the B' best raw scores (plus, harmlessly, up to kSelSmall more that share the 22-bit
 //                prefix of the last one)
-//   seed_rank    per seed: its rank among the seeds (counting, 16 lanes a seed) and the nearest seed that
-//                outranks it on either side (a scan of the raw scores around it: whatever outranks a seed
-//                is a seed)
+//   seed_rank    per seed: its rank among the seeds (counting: a wavefront's lanes share out the staged keys
+//                and compare them with its four seeds) and the nearest seed that outranks it on either side
+//                (a scan of the raw scores around it, 16 lanes a seed: whatever outranks a seed is a seed)
 //   seed_lists   one workgroup per kernel size: seed u owns the tokens whose window holds u and no seed
 //                that outranks u, an interval [max(u-r, a+r+1), min(u+r, b-r-1)]; their pooled value is
 //                u's score.  Seeds in rank order, each interval ascending, is the kernel size's ranked
