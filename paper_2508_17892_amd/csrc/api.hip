@@ -32,7 +32,7 @@ int fail(int status, const char *fmt, ...)
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t part_m, part_z, flag, row_max, row_sumexp, partial, select, total;
+    size_t part_m, part_z, flag, row_max, row_sumexp, row_off, partial, select, total;
     ilre::SelectLayout sel;
 };
 
@@ -78,6 +78,8 @@ Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, const ilr
     off = up256(off + (size_t)nrows * sizeof(float));
     l.row_sumexp = off;
     off = up256(off + (size_t)nrows * sizeof(float));
+    l.row_off = off;
+    off = up256(off + (size_t)p.nunits * p.rows_per_wg * sizeof(float));
     l.partial = off;
     off = up256(off + (size_t)p.nunits * (size_t)L * sizeof(float));
     l.select = off;
@@ -344,6 +346,7 @@ int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, i
     unsigned char *ws = (unsigned char *)opts->workspace;
     a.row_max = row_max;
     a.row_sumexp = row_sumexp;
+    a.row_off = (float *)(ws + lay.row_off);
     a.partial = (float *)(ws + lay.partial);
     a.dump = (float *)(ws + lay.flag) + 16;
     const hipError_t e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, (hipStream_t)opts->stream);
@@ -408,13 +411,14 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     a.part_z = (float *)(ws + lay.part_z);
     float *row_max = (float *)(ws + lay.row_max);
     float *row_sumexp = (float *)(ws + lay.row_sumexp);
-    hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, s);
+    a.row_off = (float *)(ws + lay.row_off);
+    hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, s, true);
     if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
     a.row_max = row_max;
     a.row_sumexp = row_sumexp;
     a.partial = (float *)(ws + lay.partial);
     a.dump = (float *)(ws + lay.flag) + 16;
-    e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s, false);
+    e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, s, false, true);
     if (e != hipSuccess) return hip_fail(e, "column-score launch");
     fused = ilre::FusedScores{a.partial, p.nunits, opts->score_mode == ILRE_SCORE_MAX ? 1 : 0, out_scores, L};
     return ILRE_OK;

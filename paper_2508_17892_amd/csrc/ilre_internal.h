@@ -47,18 +47,21 @@ struct ScoreArgs {
     int force_online;        // 1: follow the running maximum throughout (the always-safe form)
     // pass 2 (column scores)
     const float *row_max, *row_sumexp;  // [Hq*Lq]
+    float *row_off;                     // [nunits][rows_per_wg]: pass 2's exponent offsets in workgroup order
     float *partial;                     // [nunits][L]
     float *dump;                        // 16 floats nobody reads: target of stores that have nothing to store
 };
 
 ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv);
 
+// offsets = true also fills a.row_off, the table of pass 2's per-row exponent offsets, for a launch_col_scores
+// with have_offsets = true behind it (otherwise launch_col_scores derives the table from row_max / row_sumexp).
 hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp,
-                            hipStream_t s);
+                            hipStream_t s, bool offsets = false);
 // reduce = false leaves the per-unit partial score vectors in a.partial for launch_reduce_units (or for the
 // selection's first pass, which can do the reduction on its way).
 hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores,
-                             hipStream_t s, bool reduce = true);
+                             hipStream_t s, bool reduce = true, bool have_offsets = false);
 hipError_t launch_reduce_units(const float *partial, int nunits, int64_t L, int rmax, float *out_scores, hipStream_t s);
 
 // ---------------------------------------------------------------- selection (Algorithm 1)

@@ -253,17 +253,19 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
             for (int k = 0; k < 4; ++k) z[b][k] = 0.f;
         }
     } else {
+        // the workgroup's slice of the offset table (filled before this launch: one entry per query row in the
+        // order the workgroups own them, -inf for padded rows, whose q = 0: exp2(0*c - inf) = 0); accumulator
+        // registers 4j .. 4j+3 of a lane are four consecutive rows
+        const float4 *off4 = (const float4 *)(a.row_off + (int64_t)unit * (WAVES * NB * 32) + wave * (NB * 32));
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rl = rl0 + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                float off = -INFINITY;  // padded rows have q = 0: exp2(0*c - inf) = 0
-                if (rl < a.rows_per_group) {
-                    const int64_t r = (int64_t)(g * a.G + rl / a.Lq) * a.Lq + rl % a.Lq;
-                    off = -(a.row_max[r] * kLog2e + __log2f(a.row_sumexp[r]));
-                }
-                noff[b][v] = off;
+            for (int j = 0; j < 4; ++j) {
+                const float4 x = off4[(b * 32 + 8 * j + 4 * half) / 4];
+                noff[b][4 * j + 0] = x.x;
+                noff[b][4 * j + 1] = x.y;
+                noff[b][4 * j + 2] = x.z;
+                noff[b][4 * j + 3] = x.w;
             }
         }
     }
@@ -495,20 +497,46 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     }
 }
 
+// Pass 2's per-row exponent offsets, -(max*log2e + log2 sum), laid out in the order the workgroups own the rows:
+// entry (unit, local) is row `qb*rows_per_wg + local` of kv head g's group, unit = g*nqb + qb; rows past the
+// group's last one (padding of the last query block) get -inf.  Done once here rather than by every lane of
+// every workgroup of the column-score kernel, whose row indices cost two integer divisions each.
+__global__ __launch_bounds__(256) void row_offsets_kernel(const float *row_max, const float *row_sumexp, float *row_off, int entries,
+                                                          int rows_per_wg, int nqb, int rows_per_group, int G, int Lq)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= entries) return;
+    const int unit = e / rows_per_wg, local = e % rows_per_wg;
+    const int g = unit / nqb, qb = unit % nqb;
+    const int rl = qb * rows_per_wg + local;
+    float off = -INFINITY;
+    if (rl < rows_per_group) {
+        const int64_t r = (int64_t)(g * G + rl / Lq) * Lq + rl % Lq;
+        off = -(row_max[r] * kLog2e + __log2f(row_sumexp[r]));
+    }
+    row_off[e] = off;
+}
+
 // Merge the per-split partial statistics of each row (fixed order) and convert to the natural-log units of
 // Eq. 4: row_max = a reference <= max_t logit, row_sumexp = sum_t exp(logit - row_max).
 // Sixteen lanes share a row and the splits among them, so that all of a row's partials are fetched in one
 // round of loads (a thread a row would fetch them in a chain of memory latencies: this kernel sits between
 // the two scoring passes and is all latency).
 constexpr int kCombineLanes = 16;
+// Where the offset of row rl of kv head g's group sits in pass 2's table (see row_offsets_kernel).
+struct OffsetTable {
+    float *row_off;  // null: not wanted
+    int group_entries;  // nqb * rows_per_wg: entries per kv head, of which the first rows_per_group are rows
+    int rows_per_group, G, Lq, Hkv;
+};
 __global__ __launch_bounds__(256) void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows,
-                                                         float *row_max, float *row_sumexp)
+                                                         float *row_max, float *row_sumexp, const OffsetTable tab)
 {
     constexpr int kBlock = 4;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t r = gid / kCombineLanes;
     const int sub = (int)(gid % kCombineLanes);
-    const int64_t rr = r < nrows ? r : nrows - 1;  // surplus groups redo the last row and store nothing
+    const int64_t rr = r < nrows ? r : nrows - 1;  // surplus groups redo the last row and store no statistics
     float mm = kNegBig;
     for (int s0 = sub; s0 < nsplit; s0 += kCombineLanes * kBlock) {
         float m[kBlock];
@@ -538,9 +566,22 @@ __global__ __launch_bounds__(256) void combine_row_stats(const float *part_m, co
     }
 #pragma unroll
     for (int o = 1; o < kCombineLanes; o <<= 1) zz += __shfl_xor(zz, o);
-    if (sub == 0 && r < nrows) {
+    if (sub != 0) return;
+    if (r < nrows) {
         row_max[r] = mm * kLn2;
         row_sumexp[r] = zz;
+        if (tab.row_off) {
+            // the same value row_offsets_kernel derives from the two outputs just written
+            const int h = (int)(r / tab.Lq), i = (int)(r % tab.Lq);
+            const int rl = (h % tab.G) * tab.Lq + i;
+            tab.row_off[(int64_t)(h / tab.G) * tab.group_entries + rl] = -((mm * kLn2) * kLog2e + __log2f(zz));
+        }
+    } else if (tab.row_off) {
+        // surplus groups fill the table's padding (rows past a group's last one)
+        const int pad_per_group = tab.group_entries - tab.rows_per_group;
+        const int64_t p = r - nrows;
+        if (p < (int64_t)pad_per_group * tab.Hkv)
+            tab.row_off[(p / pad_per_group) * tab.group_entries + tab.rows_per_group + p % pad_per_group] = -INFINITY;
     }
 }
 
@@ -638,7 +679,7 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     return p;
 }
 
-hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp, hipStream_t s)
+hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_max, float *row_sumexp, hipStream_t s, bool offsets)
 {
     // One launch: a workgroup whose sums against frozen references leave the safe range walks its split a second
     // time in the always-safe form before it writes its partials.
@@ -652,8 +693,11 @@ hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_m
     else
         e = launch_score(score_kernel<ILRE_BF16, 2, 8, 0, 0>, p.grid, 512, lds, a, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((nrows * kCombineLanes + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
-                       a.nsplit, nrows, row_max, row_sumexp);
+    const OffsetTable tab{offsets ? a.row_off : nullptr, p.nqb * p.rows_per_wg, p.rows_per_group, a.G, a.Lq, a.Hkv};
+    // one 16-lane group per row, and with the table one more per padded table entry
+    const int64_t groups = nrows + (offsets ? (int64_t)(tab.group_entries - tab.rows_per_group) * a.Hkv : 0);
+    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((groups * kCombineLanes + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
+                       a.nsplit, nrows, row_max, row_sumexp, tab);
     return hipGetLastError();
 }
 
@@ -667,11 +711,17 @@ hipError_t launch_reduce_units(const float *partial, int nunits, int64_t L, int 
     return hipGetLastError();
 }
 
-hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s, bool reduce)
+hipError_t launch_col_scores(const ScorePlan &p, const ScoreArgs &a, int score_mode, float *out_scores, hipStream_t s, bool reduce,
+                             bool have_offsets)
 {
     hipError_t e;
     const size_t lds = p.lds_bytes_cols;
     const bool mx = score_mode == ILRE_SCORE_MAX;
+    if (!have_offsets) {
+        const int entries = p.nunits * p.rows_per_wg;
+        hipLaunchKernelGGL(row_offsets_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, s, a.row_max, a.row_sumexp,
+                           a.row_off, entries, p.rows_per_wg, p.nqb, p.rows_per_group, a.G, a.Lq);
+    }
     if (p.dtype == ILRE_F32)
         e = mx ? launch_score(score_kernel<ILRE_F32, 1, 4, 1, 1>, p.grid, 256, lds, a, s)
                : launch_score(score_kernel<ILRE_F32, 1, 4, 1, 0>, p.grid, 256, lds, a, s);
