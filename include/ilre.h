@@ -119,7 +119,9 @@ int ilre_recall(const void *q, const void *k_cache,
        row_sumexp[r] = sum_t exp(logit[r,t] - row_ref[r]),   log sum_t exp(logit[r,t]) = row_ref[r] + log row_sumexp[r].
    row_ref[r] <= max_t logit[r,t]; it equals the maximum with ILRE_FLAG_EXACT_ROW_MAX, otherwise it is
    the maximum over the first tokens of the row's context splits (row_sumexp stays finite: a part of the
-   context whose sums would leave the safe range is walked again against the running maximum).  Both dev, Hq*Lq float. */
+   context whose sums would leave the safe range is walked again against the running maximum).  Both dev, Hq*Lq float.
+   Needs the head of the workspace only (the partial statistics); given a workspace of ilre_workspace_bytes it
+   also leaves there, on long contexts, how fast each part of the chip ran, for a later ilre_col_scores. */
 int ilre_row_stats(const void *q, const void *k_cache,
                    int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                    float *row_ref, float *row_sumexp, const ilre_opts *opts);
@@ -139,7 +141,10 @@ int ilre_row_stats_static(const void *q, const void *k_cache,
 
 /* Stage 2 (Eq. 4 normalised, Eq. 5): recompute the logits, normalise with the given row
    statistics (any pair with the right row_ref + log row_sumexp) and reduce over heads and queries.
-   row_ref,row_sumexp: dev, as written by ilre_row_stats.  out_scores: dev, L float. */
+   row_ref,row_sumexp: dev, as written by ilre_row_stats.  out_scores: dev, L float.
+   On long contexts, a workspace in which an ilre_row_stats call of the same shape left its timings lets this call
+   size each workgroup's token range by the speed of the XCD it runs on; the scores are the same bits with or
+   without (the table is recognised by a header and ignored otherwise, whatever the workspace holds). */
 int ilre_col_scores(const void *q, const void *k_cache,
                     int64_t L, int32_t Lq, int32_t Hq, int32_t Hkv, int32_t d,
                     const float *row_ref, const float *row_sumexp,

@@ -32,7 +32,7 @@ int fail(int status, const char *fmt, ...)
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t part_m, part_z, flag, row_max, row_sumexp, row_off, partial, select, total;
+    size_t part_m, part_z, flag, row_max, row_sumexp, row_off, wg_time, split_table, partial, select, total;
     ilre::SelectLayout sel;
 };
 
@@ -80,6 +80,10 @@ Layout make_layout(const ilre::ScorePlan &p, int64_t L, int64_t nrows, const ilr
     off = up256(off + (size_t)nrows * sizeof(float));
     l.row_off = off;
     off = up256(off + (size_t)p.nunits * p.rows_per_wg * sizeof(float));
+    l.wg_time = off;
+    off = up256(off + (size_t)p.grid * sizeof(uint32_t));
+    l.split_table = off;
+    off = up256(off + ((size_t)p.nsplit + 3) * sizeof(int32_t));
     l.partial = off;
     off = up256(off + (size_t)p.nunits * (size_t)L * sizeof(float));
     l.select = off;
@@ -219,6 +223,7 @@ void fill_plan(ilre::ScoreArgs &a, const ilre::ScorePlan &p)
     a.nsplit = p.nsplit;
     a.ntiles = p.ntiles;
     a.tiles_per_split = p.tiles_per_split;
+    a.table_tag = p.table_tag;
 }
 
 int hip_fail(hipError_t e, const char *what)
@@ -279,6 +284,12 @@ int row_stats_into(const void *q, const void *k_cache, int64_t L, int32_t Lq, in
     fill_plan(a, p);
     a.part_m = (float *)(ws + lay.part_m);
     a.part_z = (float *)(ws + lay.part_z);
+    // a workspace that also serves ilre_col_scores is told how fast each XCD was (that call sizes its token
+    // ranges by it); one that only holds this call's scratch is not
+    if (!static_buf && p.balanced && opts->workspace_bytes >= lay.partial) {
+        a.wg_time = (uint32_t *)(ws + lay.wg_time);
+        a.split_table = (int32_t *)(ws + lay.split_table);
+    }
     const hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, (hipStream_t)opts->stream);
     if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
     return ILRE_OK;
@@ -347,6 +358,7 @@ int ilre_col_scores(const void *q, const void *k_cache, int64_t L, int32_t Lq, i
     a.row_max = row_max;
     a.row_sumexp = row_sumexp;
     a.row_off = (float *)(ws + lay.row_off);
+    if (p.balanced) a.split_table = (int32_t *)(ws + lay.split_table);  // taken only if an ilre_row_stats of this shape left it there
     a.partial = (float *)(ws + lay.partial);
     a.dump = (float *)(ws + lay.flag) + 16;
     const hipError_t e = ilre::launch_col_scores(p, a, opts->score_mode, out_scores, (hipStream_t)opts->stream);
@@ -412,6 +424,10 @@ int run_scoring(const void *q, const void *k_cache, int64_t L, int32_t Lq, int32
     float *row_max = (float *)(ws + lay.row_max);
     float *row_sumexp = (float *)(ws + lay.row_sumexp);
     a.row_off = (float *)(ws + lay.row_off);
+    if (p.balanced) {
+        a.wg_time = (uint32_t *)(ws + lay.wg_time);
+        a.split_table = (int32_t *)(ws + lay.split_table);
+    }
     hipError_t e = ilre::launch_row_stats(p, a, row_max, row_sumexp, s, true);
     if (e != hipSuccess) return hip_fail(e, "row-statistics launch");
     a.row_max = row_max;

@@ -30,6 +30,8 @@ struct ScorePlan {
     int64_t tiles_per_split;
     int nunits;           // Hkv * nqb  (partial score vectors of pass 2)
     int grid;             // workgroups launched (a few may be idle padding for the XCD mapping)
+    bool balanced;        // pass 2's token ranges are sized by the XCDs' speed in pass 1
+    uint64_t table_tag;   // header of a range table made for this plan
     size_t lds_bytes_stats, lds_bytes_cols;
 };
 
@@ -45,6 +47,9 @@ struct ScoreArgs {
     // pass 1 (row statistics): per-split partial maxima (base-2 units) and sums
     float *part_m, *part_z;  // [nsplit][Hq*Lq]
     int force_online;        // 1: follow the running maximum throughout (the always-safe form)
+    uint32_t *wg_time;       // [grid] how long each workgroup of pass 1 ran, 10 ns ticks (null: not recorded)
+    int32_t *split_table;    // [2 + nsplit + 1] pass 2's token ranges: written behind pass 1, read by pass 2 (null: even ranges)
+    uint64_t table_tag;
     // pass 2 (column scores)
     const float *row_max, *row_sumexp;  // [Hq*Lq]
     float *row_off;                     // [nunits][rows_per_wg]: pass 2's exponent offsets in workgroup order

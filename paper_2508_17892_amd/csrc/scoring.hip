@@ -169,11 +169,30 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     const int slot = blockIdx.x / kNumXCD;
     const int qb = slot % a.nqb;
     const int64_t pair = (int64_t)(slot / a.nqb) * kNumXCD + xcd;
+    // Pass 1 notes how long each workgroup ran (0: it had nothing to do); the merge kernel behind it turns the
+    // times into pass 2's token ranges.
+    const bool timed = MODE == 0 && a.wg_time != nullptr && threadIdx.x == 0;
+    const unsigned long long t_begin = timed ? wall_clock64() : 0ull;
+    if (timed) a.wg_time[blockIdx.x] = 0u;
     if (pair >= (int64_t)a.Hkv * a.nsplit) return;
     const int g = (int)(pair / a.nsplit);
     const int split = (int)(pair % a.nsplit);
-    const int64_t tile0 = (int64_t)split * a.tiles_per_split;
-    const int64_t tile1 = (tile0 + a.tiles_per_split < a.ntiles) ? tile0 + a.tiles_per_split : a.ntiles;
+    int64_t tile_lo = (int64_t)split * a.tiles_per_split;
+    int64_t tile_hi = (tile_lo + a.tiles_per_split < a.ntiles) ? tile_lo + a.tiles_per_split : a.ntiles;
+    if (MODE == 1 && a.split_table != nullptr) {
+        // Pass 2's column results do not depend on how the tokens are cut into ranges, so the ranges may follow the
+        // speed of the XCD they run on (the table's header says which launch shape it was made for; whatever it
+        // holds, a range is only taken if it lies inside the context).
+        const int32_t *tb = a.split_table;
+        if ((uint32_t)tb[0] == (uint32_t)a.table_tag && (uint32_t)tb[1] == (uint32_t)(a.table_tag >> 32)) {
+            const int64_t b0 = tb[2 + split], b1 = tb[3 + split];
+            if (b0 >= 0 && b0 <= b1 && b1 <= a.ntiles) {
+                tile_lo = b0;
+                tile_hi = b1;
+            }
+        }
+    }
+    const int64_t tile0 = tile_lo, tile1 = tile_hi;
     if (tile0 >= tile1) return;
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -494,6 +513,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
                 a.part_z[(int64_t)split * nrows + r] = zz;
             }
         }
+        if (timed) {
+            const unsigned long long dt = wall_clock64() - t_begin;  // 10 ns ticks
+            a.wg_time[blockIdx.x] = dt < 0xFFFFFFFFull ? (uint32_t)(dt ? dt : 1) : 0xFFFFFFFFu;
+        }
     }
 }
 
@@ -524,15 +547,102 @@ __global__ __launch_bounds__(256) void row_offsets_kernel(const float *row_max, 
 // the two scoring passes and is all latency).
 constexpr int kCombineLanes = 16;
 // Where the offset of row rl of kv head g's group sits in pass 2's table (see row_offsets_kernel).
+// Pass 2's token ranges from pass 1's workgroup times.  The 8 XCDs of the chip do not run at one speed (their
+// workgroups finish up to 6 % apart, the same dies ahead in every launch), and a launch lasts as long as its
+// slowest XCD.  Split s of every kv head runs on the same XCD when the splits per head are a multiple of 8, so
+// the ranges are sized by the mean time the workgroups of split s took in pass 1: range s gets a share of the
+// tiles proportional to 1 / time, within 15 % of an even share (a workgroup that walked its split twice, or a
+// disturbed launch, must not skew the next one).  Only pass 2 is cut this way: its results do not depend on the
+// cut, pass 1's rounding would.
+constexpr int kMaxBalancedSplits = 512;
+struct BalanceArgs {
+    const uint32_t *wg_time;  // null: no table wanted
+    int32_t *table;           // [2 + nsplit + 1]: tag (low, high), then the first tile of every range and ntiles
+    uint64_t tag;
+    int grid, nqb, nsplit, Hkv;
+    int64_t ntiles;
+};
+__device__ void make_split_table(const BalanceArgs &b)
+{
+    __shared__ uint32_t sum[kMaxBalancedSplits], cnt[kMaxBalancedSplits];
+    for (int s = threadIdx.x; s < b.nsplit; s += blockDim.x) sum[s] = cnt[s] = 0;
+    __syncthreads();
+    for (int w = threadIdx.x; w < b.grid; w += blockDim.x) {
+        const uint32_t t = b.wg_time[w];
+        const int64_t pair = (int64_t)((w / kNumXCD) / b.nqb) * kNumXCD + w % kNumXCD;
+        if (t != 0 && pair < (int64_t)b.Hkv * b.nsplit) {
+            atomicAdd(&sum[pair % b.nsplit], t >> 4);  // 160 ns units: the sum over all workgroups of a split fits
+            atomicAdd(&cnt[pair % b.nsplit], 1u);
+        }
+    }
+    __syncthreads();
+    // One wavefront, eight splits a lane: mean time per split, weight = mean of those over the split's own,
+    // running sum of the weights, edges.  (One thread doing this in a loop was a 20 us chain at 32 splits.)
+    if (threadIdx.x >= 64) return;
+    constexpr int kPer = kMaxBalancedSplits / 64;
+    const int lane = threadIdx.x;
+    float d[kPer], lsum = 0.f, lcnt = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const int sp = lane * kPer + k;
+        d[k] = (sp < b.nsplit && cnt[sp] && sum[sp]) ? (float)sum[sp] / (float)cnt[sp] : 0.f;
+        lsum += d[k];
+        lcnt += d[k] > 0.f ? 1.f : 0.f;
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        lsum += __shfl_xor(lsum, o);
+        lcnt += __shfl_xor(lcnt, o);
+    }
+    const float mean = lcnt > 0.f ? lsum / lcnt : 1.f;
+    float w[kPer], lw = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const int sp = lane * kPer + k;
+        float x = d[k] > 0.f ? mean / d[k] : 1.f;
+        x = x < 0.85f ? 0.85f : (x > 1.15f ? 1.15f : x);
+        w[k] = sp < b.nsplit ? x : 0.f;
+        lw += w[k];
+    }
+    float incl = lw;  // inclusive running sum over the lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    const float weights = __shfl(incl, 63);
+    float upto = incl - lw;
+    if (lane == 0) {
+        b.table[0] = (int32_t)(uint32_t)b.tag;
+        b.table[1] = (int32_t)(uint32_t)(b.tag >> 32);
+        b.table[2] = 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const int sp = lane * kPer + k;
+        upto += w[k];
+        if (sp < b.nsplit) {
+            int64_t edge = (int64_t)((double)b.ntiles * (double)(upto / weights) + 0.5);
+            if (edge > b.ntiles || sp == b.nsplit - 1) edge = b.ntiles;
+            b.table[3 + sp] = (int32_t)edge;  // non-decreasing: the running sum is, and so are the steps behind it
+        }
+    }
+}
+
 struct OffsetTable {
     float *row_off;  // null: not wanted
     int group_entries;  // nqb * rows_per_wg: entries per kv head, of which the first rows_per_group are rows
     int rows_per_group, G, Lq, Hkv;
 };
 __global__ __launch_bounds__(256) void combine_row_stats(const float *part_m, const float *part_z, int nsplit, int64_t nrows,
-                                                         float *row_max, float *row_sumexp, const OffsetTable tab)
+                                                         float *row_max, float *row_sumexp, const OffsetTable tab,
+                                                         const BalanceArgs bal)
 {
     constexpr int kBlock = 4;
+    if (bal.wg_time && blockIdx.x == gridDim.x - 1) {  // the launch's last workgroup is there for the table alone
+        make_split_table(bal);
+        return;
+    }
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t r = gid / kCombineLanes;
     const int sub = (int)(gid % kCombineLanes);
@@ -674,6 +784,13 @@ ScorePlan make_score_plan(int dtype, int64_t L, int Lq, int Hq, int Hkv)
     const int64_t pairs = (int64_t)Hkv * p.nsplit;
     p.grid = (int)(((pairs + kNumXCD - 1) / kNumXCD) * kNumXCD * p.nqb);
     const size_t tiles = dtype == ILRE_F32 ? tile_lds_bytes<ILRE_F32>(p.waves) : tile_lds_bytes<ILRE_BF16>(p.waves);
+    // pass 2's ranges follow the XCDs' speed where a range is long enough for that to matter
+    p.balanced = p.tiles_per_split >= 64 && p.nsplit >= kNumXCD && p.nsplit <= kMaxBalancedSplits;
+    uint64_t tag = 0x494c52652d584344ull;  // what a table has to have been made for
+    for (uint64_t v : {(uint64_t)L, (uint64_t)p.ntiles, (uint64_t)p.nsplit, (uint64_t)p.nqb, (uint64_t)Hkv, (uint64_t)p.tile_tokens,
+                       (uint64_t)p.grid})
+        tag = (tag ^ v) * 0x9E3779B97F4A7C15ull + 0x7F4A7C15ull;
+    p.table_tag = tag;
     p.lds_bytes_stats = tiles;
     p.lds_bytes_cols = tiles + 3 * 2 * (size_t)p.waves * (p.tile_tokens + 36) * sizeof(float);  // pitch <= tokens + 36
     return p;
@@ -696,8 +813,10 @@ hipError_t launch_row_stats(const ScorePlan &p, const ScoreArgs &a, float *row_m
     const OffsetTable tab{offsets ? a.row_off : nullptr, p.nqb * p.rows_per_wg, p.rows_per_group, a.G, a.Lq, a.Hkv};
     // one 16-lane group per row, and with the table one more per padded table entry
     const int64_t groups = nrows + (offsets ? (int64_t)(tab.group_entries - tab.rows_per_group) * a.Hkv : 0);
-    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((groups * kCombineLanes + 255) / 256)), dim3(256), 0, s, a.part_m, a.part_z,
-                       a.nsplit, nrows, row_max, row_sumexp, tab);
+    const bool balance = a.wg_time != nullptr && a.split_table != nullptr;
+    const BalanceArgs bal{balance ? a.wg_time : nullptr, a.split_table, a.table_tag, p.grid, p.nqb, p.nsplit, a.Hkv, p.ntiles};
+    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((groups * kCombineLanes + 255) / 256) + (balance ? 1u : 0u)), dim3(256), 0, s,
+                       a.part_m, a.part_z, a.nsplit, nrows, row_max, row_sumexp, tab, bal);
     return hipGetLastError();
 }
 

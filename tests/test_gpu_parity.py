@@ -397,6 +397,33 @@ def test_bitwise_reproducible():
         assert torch.equal(first[0], again[0]) and torch.equal(first[1], again[1])
 
 
+def test_column_scores_do_not_depend_on_how_the_tokens_are_cut():
+    """Long contexts: the second scoring pass sizes each workgroup's token range by how fast its XCD ran the first
+    pass (a table the first pass leaves in the workspace).  The scores must be the same bits with that table, without
+    it (a workspace nothing was left in), with a workspace full of noise, and inside the whole path."""
+    _announce("second pass: token ranges from the XCDs' speed vs even ranges")
+    L, Lq, Hq, Hkv = 1100000, 64, 8, 2   # 253 token ranges of 68 tiles (64 tokens each) per kv head
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    q = torch.randn(Hq, Lq, 128, device="cuda", generator=g).to(torch.bfloat16)
+    k = torch.randn(Hkv, L, 128, device="cuda", generator=g).to(torch.bfloat16)
+    nbytes = il.ilre_workspace_bytes(L, Lq, Hq, Hkv, 128, 5, il.ILRE_BF16)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    rmax, rsum = il.ilre_row_stats(q, k, workspace=ws)
+    with_table = il.ilre_col_scores(q, k, rmax, rsum, workspace=ws).clone()
+    clean = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    without = il.ilre_col_scores(q, k, rmax, rsum, workspace=clean).clone()
+    noise = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=g)
+    noisy = il.ilre_col_scores(q, k, rmax, rsum, workspace=noise).clone()
+    idx, whole = il.ilre_recall(q, k, 2048, (1, 3, 7, 15, 31), workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(with_table, without)
+    assert torch.equal(with_table, noisy)
+    assert torch.equal(with_table, whole)
+    total = float(with_table.double().sum())
+    assert abs(total - Hq * Lq) < 1e-3 * Hq * Lq  # every softmax row sums to one (Section 3.2, Eq. 4)
+
+
 def test_custom_scale():
     _announce("custom softmax scale")
     inp = inputs.custom(L=1500, Lq=8, Hq=4, Hkv=2, d=128, dtype="bf16", seed=8)
