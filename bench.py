@@ -64,11 +64,14 @@ def mfma_ceiling(il, torch, launches: int = 5, iters: int = 2000) -> dict:
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / launches
             clk = out[1 << 20:(1 << 20) + 4096].view(torch.int64).view(256, 2).double().cpu()
-            ghz = float((clk[:, 0] / clk[:, 1]).mean()) * 0.1          # cycles per 10 ns tick
+            per_wg = clk[:, 0] / clk[:, 1] * 0.1                       # cycles per 10 ns tick
+            ghz = float(per_wg.mean())
+            # workgroup b runs on XCD b mod 8: the dies do not hold the same clock under load
+            by_xcd = [round(float(per_wg[x::8].mean()), 3) for x in range(8)]
             tf = flops / (ms * 1e-3) / 1e12
             rows.append({"variant": variant, "what": il.ilre_probe_describe(variant), "operands": name,
                          "ms": round(ms, 4), "tflops": round(tf, 1), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
-                         "clock_ghz": round(ghz, 3),
+                         "clock_ghz": round(ghz, 3), "clock_ghz_by_xcd": by_xcd,
                          # the MFMA pipe's share of the cycles at the measured clock; for the loops without MFMAs,
                          # the same ratio for the MFMAs that were left out (above 1: the vector work alone is faster)
                          "mfma_busy": round(tf / (PEAK_BF16_TFLOPS * ghz / 2.4), 4) if ghz > 0 else None})
