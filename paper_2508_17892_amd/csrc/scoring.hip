@@ -181,14 +181,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void score_kernel(const ScoreArgs a)
     int64_t tile_hi = (tile_lo + a.tiles_per_split < a.ntiles) ? tile_lo + a.tiles_per_split : a.ntiles;
     if (MODE == 1 && a.split_table != nullptr) {
         // Pass 2's column results do not depend on how the tokens are cut into ranges, so the ranges may follow the
-        // speed of the XCD they run on (the table's header says which launch shape it was made for; whatever it
-        // holds, a range is only taken if it lies inside the context).
+        // speed of the XCD they run on (the table's header says which launch shape it was made for; the table is
+        // only used if it is a cut of the context, whatever the workspace holds).
         const int32_t *tb = a.split_table;
         if ((uint32_t)tb[0] == (uint32_t)a.table_tag && (uint32_t)tb[1] == (uint32_t)(a.table_tag >> 32)) {
-            const int64_t b0 = tb[2 + split], b1 = tb[3 + split];
-            if (b0 >= 0 && b0 <= b1 && b1 <= a.ntiles) {
-                tile_lo = b0;
-                tile_hi = b1;
+            // every wavefront checks the whole table (a few loads a lane): edges from 0 to ntiles that never
+            // step back cut the context into ranges that cover every tile once, whatever else they are
+            bool bad = false;
+            for (int i = threadIdx.x & 63; i <= a.nsplit; i += 64) {
+                const int64_t e0 = tb[2 + i], e1 = i < a.nsplit ? (int64_t)tb[3 + i] : a.ntiles;
+                bad = bad || e0 < 0 || e0 > e1 || e1 > a.ntiles || (i == 0 && e0 != 0) || (i == a.nsplit && e0 != a.ntiles);
+            }
+            if (!__any(bad)) {
+                tile_lo = tb[2 + split];
+                tile_hi = tb[3 + split];
             }
         }
     }

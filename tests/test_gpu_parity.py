@@ -416,10 +416,15 @@ def test_column_scores_do_not_depend_on_how_the_tokens_are_cut():
     noise = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=g)
     noisy = il.ilre_col_scores(q, k, rmax, rsum, workspace=noise).clone()
     idx, whole = il.ilre_recall(q, k, 2048, (1, 3, 7, 15, 31), workspace=ws)
+    # a stand-alone selection uses the workspace from its base and may write over what the first pass left there
+    il.ilre_row_stats(q, k, workspace=ws)
+    il.ilre_select(whole, 2048, (1, 3, 7, 15, 31), workspace=ws)
+    after_select = il.ilre_col_scores(q, k, rmax, rsum, workspace=ws).clone()
     torch.cuda.synchronize()
     assert torch.equal(with_table, without)
     assert torch.equal(with_table, noisy)
     assert torch.equal(with_table, whole)
+    assert torch.equal(with_table, after_select)
     total = float(with_table.double().sum())
     assert abs(total - Hq * Lq) < 1e-3 * Hq * Lq  # every softmax row sums to one (Section 3.2, Eq. 4)
 
